@@ -1,0 +1,289 @@
+"""Float64 CPU oracle for multi-query / multi-head attention decoding.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+HIP kernels are checked against.  It shares no code with them and nothing in
+the product path may import it; only tests, the smoke check and the
+benchmark's CPU-baseline leg call it.
+
+Everything is numpy float64.  Each function states the passage of the paper
+(arXiv 1911.02150) it writes out.  The paper's method is exact attention with
+the heads dimension removed from K and V, so the oracle is that definition:
+einsum contractions ("broadcast, multiply, sum", Section 2.1) and a softmax
+over the memory positions.  No blocking, fusion or reordering.
+
+Readings taken where the paper's listings are silent or garbled:
+  * Section 2.4 / Section 3 incremental listings project an undefined `M` and
+    return an undefined `O`: read as the step input `x` and the heads' outputs
+    `o` (self-attention: the new memory row comes from the current input).
+  * The Section 3 incremental listing concatenates on axis 2 of a [b,m,k]
+    tensor; its declared result [b,m+1,k] fixes the position axis as axis 1.
+  * No 1/sqrt(k) logit scale (Section 2.2 note): `scale` defaults to 1.
+  * softmax runs over the last (memory position) axis, per (sequence, head).
+  * The new token attends to itself (logits use the concatenated K).
+  * A sequence with no valid position yields a zero output row.
+  * The growing concat is kept as an in-place append into a capacity-sized
+    buffer with per-sequence lengths (the alternative named in the Section 4.3
+    footnote); rows at and beyond the length are never read.
+  * Cache number format is not stated by the paper; a bf16 cache stores each
+    new row rounded float32 -> bf16, round-to-nearest-even.
+
+Parity pins (tests/test_oracle_*.py): brute-force enumeration on tiny shapes,
+softmax against scipy, weights sum to one, MQA == MHA with shared K/V,
+incremental == causally masked batched attention, closed forms (one position,
+zero query, dominant logit, shift and permutation invariance, convex hull),
+torch float64 scaled-dot-product attention as an independent routine, split
+and recombine of the softmax state, NaN rows beyond the length, and bf16
+rounding against torch's cast.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# Section 2.1: softmax and single-query dot-product attention
+# --------------------------------------------------------------------------
+def softmax64(z, axis=-1):
+    """softmax over `axis` (Section 2.1, `weights = softmax(logits)`)."""
+    z = np.asarray(z, dtype=F64)
+    e = np.exp(z - np.max(z, axis=axis, keepdims=True))
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def dot_product_attention(q, K, V):
+    """Section 2.1 `DotProductAttention`: q [k], K [m,k], V [m,v] -> y [v]."""
+    q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
+    logits = np.einsum("k,mk->m", q, K)
+    weights = softmax64(logits)
+    return np.einsum("m,mv->v", weights, V)
+
+
+# --------------------------------------------------------------------------
+# Section 2.2 / Section 3: one query x against a memory M
+# --------------------------------------------------------------------------
+def multihead_attention(x, M, P_q, P_k, P_v, P_o):
+    """Section 2.2 `MultiheadAttention`: x [d], M [m,d], P_q/P_k [h,d,k],
+    P_v/P_o [h,d,v] -> y [d]."""
+    x, M, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (x, M, P_q, P_k, P_v, P_o))
+    q = np.einsum("d,hdk->hk", x, P_q)
+    K = np.einsum("md,hdk->hmk", M, P_k)
+    V = np.einsum("md,hdv->hmv", M, P_v)
+    logits = np.einsum("hk,hmk->hm", q, K)
+    weights = softmax64(logits)
+    o = np.einsum("hm,hmv->hv", weights, V)
+    return np.einsum("hv,hdv->d", o, P_o)
+
+
+def multiquery_attention(x, M, P_q, P_k, P_v, P_o):
+    """Section 3 rule applied to the Section 2.2 listing: the letter h is
+    dropped where it indexes K, V, P_k, P_v.  P_k [d,k], P_v [d,v]."""
+    x, M, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (x, M, P_q, P_k, P_v, P_o))
+    q = np.einsum("d,hdk->hk", x, P_q)
+    K = np.einsum("md,dk->mk", M, P_k)
+    V = np.einsum("md,dv->mv", M, P_v)
+    logits = np.einsum("hk,mk->hm", q, K)
+    weights = softmax64(logits)
+    o = np.einsum("hm,mv->hv", weights, V)
+    return np.einsum("hv,hdv->d", o, P_o)
+
+
+# --------------------------------------------------------------------------
+# Section 2.3 / Section 3: batched (parallel over positions) attention
+# --------------------------------------------------------------------------
+def causal_mask(b, h, n, m=None):
+    """Additive mask of Section 2.3: 0 where position j <= i, -inf elsewhere."""
+    m = n if m is None else m
+    i = np.arange(n)[:, None]
+    j = np.arange(m)[None, :]
+    mask = np.where(j <= i, 0.0, -np.inf)
+    return np.broadcast_to(mask, (b, h, n, m)).copy()
+
+
+def multihead_attention_batched(X, M, mask, P_q, P_k, P_v, P_o, kv_round=None):
+    """Section 2.3 `MultiheadAttentionBatched`: X [b,n,d], M [b,m,d],
+    mask [b,h,n,m] -> Y [b,n,d].  `kv_round`, if given, is applied to K and V
+    (used to mirror a reduced-precision cache)."""
+    X, M, mask, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (X, M, mask, P_q, P_k, P_v, P_o))
+    Q = np.einsum("bnd,hdk->bhnk", X, P_q)
+    K = np.einsum("bmd,hdk->bhmk", M, P_k)
+    V = np.einsum("bmd,hdv->bhmv", M, P_v)
+    if kv_round is not None:
+        K, V = kv_round(K), kv_round(V)
+    logits = np.einsum("bhnk,bhmk->bhnm", Q, K)
+    weights = softmax64(logits + mask)
+    O = np.einsum("bhnm,bhmv->bhnv", weights, V)
+    return np.einsum("bhnv,hdv->bnd", O, P_o)
+
+
+def multiquery_attention_batched(X, M, mask, P_q, P_k, P_v, P_o, kv_round=None):
+    """Section 3 `MultiqueryAttentionBatched`: as above with K [b,m,k],
+    V [b,m,v], P_k [d,k], P_v [d,v]."""
+    X, M, mask, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (X, M, mask, P_q, P_k, P_v, P_o))
+    Q = np.einsum("bnd,hdk->bhnk", X, P_q)
+    K = np.einsum("bmd,dk->bmk", M, P_k)
+    V = np.einsum("bmd,dv->bmv", M, P_v)
+    if kv_round is not None:
+        K, V = kv_round(K), kv_round(V)
+    logits = np.einsum("bhnk,bmk->bhnm", Q, K)
+    weights = softmax64(logits + mask)
+    O = np.einsum("bhnm,bmv->bhnv", weights, V)
+    return np.einsum("bhnv,hdv->bnd", O, P_o)
+
+
+# --------------------------------------------------------------------------
+# the pieces of one incremental step (Section 2.4 and Section 3 listings)
+# --------------------------------------------------------------------------
+def project_q(x, P_q):
+    """q = einsum('bd,hdk->bhk') (first line of both incremental listings)."""
+    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P_q, dtype=F64))
+
+
+def project_kv(x, P):
+    """Multi-query new row: einsum('bd,dk->bk') (Section 3 incremental listing)."""
+    return np.einsum("bd,dk->bk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64))
+
+
+def project_kv_mh(x, P):
+    """Multi-head new rows: einsum('bd,hdk->bhk') (Section 2.4 listing)."""
+    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64))
+
+
+def project_o(o, P_o):
+    """y = einsum('bhv,hdv->bd') (last line of both incremental listings;
+    note P_o is [h,d,v], model width before value width)."""
+    return np.einsum("bhv,hdv->bd", np.asarray(o, dtype=F64), np.asarray(P_o, dtype=F64))
+
+
+def round_to_bf16(a):
+    """float -> nearest bfloat16 (ties to even) via float32, returned as
+    float64 holding the exactly representable value.  NaN stays NaN."""
+    f = np.ascontiguousarray(np.asarray(a, dtype=F64).astype(np.float32))
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
+    out = r.astype(np.uint32).view(np.float32).astype(F64)
+    return np.where(np.isnan(f), np.nan, out).reshape(np.shape(a))
+
+
+def round_to_f32(a):
+    return np.asarray(a, dtype=F64).astype(np.float32).astype(F64)
+
+
+_CACHE_ROUND = {"f64": lambda a: np.asarray(a, dtype=F64), "f32": round_to_f32, "bf16": round_to_bf16}
+
+
+def append_kv(K, V, k_new, v_new, lens, cache="f64"):
+    """In-place form of the listings' concat: write the new row at position
+    lens[i] of sequence i, then lens[i] += 1.  K is [b,cap,k] (multi-query,
+    k_new [b,k]) or [b,h,cap,k] (multi-head, k_new [b,h,k]); same for V.
+    A sequence already at capacity is left untouched."""
+    rnd = _CACHE_ROUND[cache]
+    k_new, v_new = rnd(k_new), rnd(v_new)
+    cap = K.shape[-2]
+    for i in range(K.shape[0]):
+        L = int(lens[i])
+        if L >= cap:
+            continue
+        K[i, ..., L, :] = k_new[i]
+        V[i, ..., L, :] = v_new[i]
+        lens[i] = L + 1
+
+
+def mqa_decode_weights(q, K, lens, scale=1.0):
+    """softmax weights of the Section 3 step: list over sequences of [h, len_i]."""
+    q, K = np.asarray(q, dtype=F64), np.asarray(K, dtype=F64)
+    out = []
+    for i in range(q.shape[0]):
+        L = int(lens[i])
+        if L == 0:
+            out.append(np.zeros((q.shape[1], 0)))
+            continue
+        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L])
+        out.append(softmax64(logits))
+    return out
+
+
+def mqa_decode(q, K, V, lens, scale=1.0):
+    """Attention part of `MultiquerySelfAttentionIncremental` (Section 3):
+    logits = einsum('bhk,bmk->bhm'), softmax over m, o = einsum('bhm,bmv->bhv'),
+    restricted per sequence to its first lens[i] positions.
+    q [b,h,k], K [b,cap,k], V [b,cap,v] -> o [b,h,v]."""
+    q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
+    b, h, _ = q.shape
+    o = np.zeros((b, h, V.shape[-1]), dtype=F64)
+    for i in range(b):
+        L = int(lens[i])
+        if L == 0:
+            continue
+        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L])
+        weights = softmax64(logits)
+        o[i] = np.einsum("hm,mv->hv", weights, V[i, :L])
+    return o
+
+
+def mha_decode(q, K, V, lens, scale=1.0):
+    """Attention part of `MultiheadSelfAttentionIncremental` (Section 2.4):
+    logits = einsum('bhk,bhmk->bhm'), softmax, o = einsum('bhm,bhmv->bhv').
+    q [b,h,k], K [b,h,cap,k], V [b,h,cap,v] -> o [b,h,v]."""
+    q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
+    b, h, _ = q.shape
+    o = np.zeros((b, h, V.shape[-1]), dtype=F64)
+    for i in range(b):
+        L = int(lens[i])
+        if L == 0:
+            continue
+        logits = scale * np.einsum("hk,hmk->hm", q[i], K[i, :, :L])
+        weights = softmax64(logits)
+        o[i] = np.einsum("hm,hmv->hv", weights, V[i, :, :L])
+    return o
+
+
+def mqa_incremental_step(x, K, V, lens, P_q, P_k, P_v, P_o, cache="f64", scale=1.0):
+    """`MultiquerySelfAttentionIncremental` (Section 3) on capacity buffers:
+    project q and the new K/V row, append (mutates K, V, lens), attend over all
+    positions including the new one, project out.  Returns (y [b,d], o, q)."""
+    q = project_q(x, P_q)
+    append_kv(K, V, project_kv(x, P_k), project_kv(x, P_v), lens, cache)
+    o = mqa_decode(q, K, V, lens, scale)
+    return project_o(o, P_o), o, q
+
+
+def mha_incremental_step(x, K, V, lens, P_q, P_k, P_v, P_o, cache="f64", scale=1.0):
+    """`MultiheadSelfAttentionIncremental` (Section 2.4) on capacity buffers."""
+    q = project_q(x, P_q)
+    append_kv(K, V, project_kv_mh(x, P_k), project_kv_mh(x, P_v), lens, cache)
+    o = mha_decode(q, K, V, lens, scale)
+    return project_o(o, P_o), o, q
+
+
+# --------------------------------------------------------------------------
+# splitting the softmax over disjoint position ranges and recombining
+# (follows from the Section 2.1 softmax definition; the GPU path's second pass)
+# --------------------------------------------------------------------------
+def partial_state(q_i, K_i, V_i, lo, hi, scale=1.0):
+    """For one sequence and positions [lo,hi): per head the maximum logit, the
+    sum of exp(logit - max) and the un-normalised weighted sum of V rows."""
+    h = q_i.shape[0]
+    if hi <= lo:
+        return np.full((h,), -np.inf), np.zeros((h,)), np.zeros((h, V_i.shape[-1]))
+    logits = scale * np.einsum("hk,mk->hm", np.asarray(q_i, F64), np.asarray(K_i[lo:hi], F64))
+    mx = logits.max(axis=1)
+    e = np.exp(logits - mx[:, None])
+    return mx, e.sum(axis=1), np.einsum("hm,mv->hv", e, np.asarray(V_i[lo:hi], F64))
+
+
+def combine_partials(states):
+    """Merge partial states (max_i, sum_i, acc_i): M = max max_i,
+    L = sum_i sum_i e^{max_i - M}, o = sum_i acc_i e^{max_i - M} / L."""
+    mx = np.stack([s[0] for s in states])            # [S,h]
+    M = mx.max(axis=0)
+    if np.all(np.isneginf(M)):
+        return np.zeros_like(states[0][2])
+    w = np.exp(mx - np.where(np.isneginf(M), 0.0, M)[None])   # [S,h]
+    L = np.sum(w * np.stack([s[1] for s in states]), axis=0)
+    acc = np.sum(w[:, :, None] * np.stack([s[2] for s in states]), axis=0)
+    with np.errstate(invalid="ignore", divide="ignore"):
+        o = acc / L[:, None]
+    return np.where(L[:, None] > 0, o, 0.0)
