@@ -1,0 +1,163 @@
+/*
+ * mqa.h - C ABI of the MI355X (gfx950) multi-query-attention decode library.
+ *
+ * The library implements one incremental decoding step of multi-query
+ * attention (arXiv 1911.02150, Section 3, `MultiquerySelfAttentionIncremental`)
+ * and, as the bandwidth comparison, of multi-head attention (Section 2.4,
+ * `MultiheadSelfAttentionIncremental`), split into the calls a decode loop
+ * makes:  project q and the new K/V row  ->  append the row to the cache  ->
+ * attend over the cache  ->  project the heads' outputs.
+ *
+ * Conventions common to every call
+ *  - All pointers are DEVICE pointers unless stated otherwise.  The caller
+ *    allocates and frees every buffer (including the workspace and `lens`);
+ *    the library never allocates, frees or synchronises.
+ *  - `stream` is the caller's hipStream_t (NULL = the default stream).  A call
+ *    validates its arguments on the host, enqueues its kernels and returns.
+ *  - Tensors are dense, row-major, innermost index last, in the paper's index
+ *    order: q [b,h,k], o [b,h,v]; multi-query cache K [b,cap,k], V [b,cap,v];
+ *    multi-head cache K [b,h,cap,k], V [b,h,cap,v]; projections P_q [h,d,k],
+ *    P_o [h,d,v] (model width before value width), multi-query P_k [d,k],
+ *    P_v [d,v], multi-head P_k [h,d,k], P_v [h,d,v].
+ *  - x, q, o, y and the projection matrices are float32.  The cache is float32
+ *    (MQA_F32) or bfloat16 (MQA_BF16); accumulation is float32.
+ *  - `cap` is the cache capacity in positions; `lens[i]` (int32, one per
+ *    sequence) is how many positions of sequence i are valid.  The paper's
+ *    growing concat (and its padded fixed-shape variant, Section 4.3 footnote)
+ *    is replaced by this capacity + length form.  Values of lens outside
+ *    [0,cap] are clamped by the kernels.
+ *  - Return value: MQA_OK (0) or a positive MQA_ERR_* code.  On error nothing
+ *    has been enqueued.  No call aborts or throws.
+ *  - Pointers must be 16-byte aligned.
+ */
+#ifndef MQA_H
+#define MQA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MQA_F32 = 0, MQA_BF16 = 1 } mqa_dtype; /* cache element type */
+
+typedef enum {
+  MQA_OK = 0,
+  MQA_ERR_NULL = 1,       /* a required pointer is NULL                         */
+  MQA_ERR_SHAPE = 2,      /* a size is non-positive or not supported            */
+  MQA_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                   */
+  MQA_ERR_WORKSPACE = 4,  /* workspace missing or smaller than required         */
+  MQA_ERR_DTYPE = 5,      /* unknown mqa_dtype / mqa_proj_mode                  */
+  MQA_ERR_LAUNCH = 6      /* the HIP runtime refused a launch                   */
+} mqa_status;
+
+typedef enum {
+  MQA_PROJ_Q = 0,     /* in [rows,d] . P [h,d,kv] -> out [rows,h,kv]  q = einsum('bd,hdk->bhk')   */
+  MQA_PROJ_KV = 1,    /* in [rows,d] . P [d,kv]   -> out [rows,kv]    einsum('bd,dk->bk'); h ignored */
+  MQA_PROJ_KV_MH = 2, /* in [rows,d] . P [h,d,kv] -> out [rows,h,kv]  multi-head new rows          */
+  MQA_PROJ_O = 3      /* in [rows,h,kv] . P [h,d,kv] -> out [rows,d]  y = einsum('bhv,hdv->bd')    */
+} mqa_proj_mode;
+
+/* Optional launch tuning for the decode calls (NULL = library heuristics). */
+typedef struct {
+  int32_t splits;   /* >0: number of position ranges each sequence is split into */
+  int32_t kernel;   /* 0 auto, 1 force the generic kernel, 2 force the MFMA kernel
+                       (MQA_ERR_SHAPE if the shape does not qualify)             */
+  int32_t flags;    /* bit 0: single bf16 term for q; bit 1: single bf16 term for
+                       the softmax weights (faster, less accurate); 0 = default  */
+} mqa_tuning;
+
+/*
+ * The four projections of the incremental listings (Section 2.4 / Section 3):
+ * first line (q), the new K and V rows, and the last line (y).  float32 in and
+ * out, float32 accumulation.  `rows` is the number of input rows (b for a
+ * decode step, b*m when projecting a whole memory M as in the Section 2.2
+ * one-query listing).  `kv` is k or v.  `out` is overwritten.
+ */
+int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,
+                     int rows, int d, int h, int kv, void* stream);
+
+/*
+ * Cache append: the in-place form of the listings' tf.concat.  For every
+ * sequence i with lens[i] < cap, writes k_new[i] / v_new[i] (converted to the
+ * cache type, round-to-nearest-even for bf16) as position lens[i] and then
+ * increments lens[i].  A sequence already at capacity is left untouched.
+ * h_kv = 1: multi-query cache, k_new [b,k], v_new [b,v].
+ * h_kv = h: multi-head cache,  k_new [b,h,k], v_new [b,h,v].
+ * K, V and lens are modified; k_new and v_new are read only.
+ */
+int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
+                  int b, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream);
+
+/*
+ * Attention of one multi-query decode step (Section 3 incremental listing,
+ * the three lines logits / weights / o):
+ *   logits[i,j,p] = scale * sum_c q[i,j,c] K[i,p,c],  p < lens[i]
+ *   weights = softmax over p,   o[i,j,:] = sum_p weights[i,j,p] V[i,p,:]
+ * Call after mqa_append_kv so that the new token attends to itself.  The paper
+ * uses scale = 1 (the 1/sqrt(k) factor is folded into P_q or P_k).
+ * lens[i] = 0 gives a zero output row.  K, V, q, lens are read only; o is
+ * overwritten; `workspace` (>= mqa_decode_workspace_bytes) holds the partial
+ * softmax states of the position ranges and is overwritten.
+ * The logits and weights never reach memory.
+ */
+int mqa_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                    int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same step for multi-head attention (Section 2.4 listing): K [b,h,cap,k],
+ * V [b,h,cap,v]; head j of sequence i reads only K[i,j], V[i,j].  Same
+ * arguments, same workspace rule (use mha_decode_workspace_bytes).
+ */
+int mha_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                    int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same as the two calls above with explicit launch tuning (NULL = defaults). */
+int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                       int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);
+int mha_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                       int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);
+
+/*
+ * The two passes of mqa_decode_step as separate calls, for measurement: the
+ * first streams K and V and leaves one partial softmax state (running maximum,
+ * sum of exponentials, un-normalised weighted sum of V rows) per position
+ * range in the workspace (or writes o directly when there is one range); the
+ * second merges the ranges: M = max m_i, L = sum l_i e^{m_i-M},
+ * o = sum acc_i e^{m_i-M} / L.  Calling them back to back on one stream is
+ * identical to mqa_decode_step_ex.
+ */
+int mqa_decode_partials(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                        int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                        void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);
+int mqa_decode_combine(const int32_t* lens, float* o, int b, int h, int cap, int k, int v, mqa_dtype dt,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);
+
+/* Workspace sizes in bytes (host-side arithmetic, valid for any tuning). */
+size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v);
+size_t mha_decode_workspace_bytes(int b, int h, int cap, int v);
+
+/* Number of position ranges the decode calls will use (host-side). multi_head = 0/1. */
+int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head,
+                          const mqa_tuning* tuning);
+
+/*
+ * Measurement helpers: a plain streaming read (every 16-byte word of `src` is
+ * loaded once; a checksum per workgroup goes to `sink`, >= 4096 floats) and a
+ * plain copy.  They give the box's achievable read / copy bandwidth and a
+ * known-size reference for scaling hardware byte counters.  bytes % 16 == 0.
+ */
+int mqa_stream_read(const void* src, size_t bytes, float* sink, void* stream);
+int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+const char* mqa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQA_H */

@@ -137,23 +137,23 @@ def multiquery_attention_batched(X, M, mask, P_q, P_k, P_v, P_o, kv_round=None):
 # --------------------------------------------------------------------------
 def project_q(x, P_q):
     """q = einsum('bd,hdk->bhk') (first line of both incremental listings)."""
-    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P_q, dtype=F64))
+    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P_q, dtype=F64), optimize=True)
 
 
 def project_kv(x, P):
     """Multi-query new row: einsum('bd,dk->bk') (Section 3 incremental listing)."""
-    return np.einsum("bd,dk->bk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64))
+    return np.einsum("bd,dk->bk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64), optimize=True)
 
 
 def project_kv_mh(x, P):
     """Multi-head new rows: einsum('bd,hdk->bhk') (Section 2.4 listing)."""
-    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64))
+    return np.einsum("bd,hdk->bhk", np.asarray(x, dtype=F64), np.asarray(P, dtype=F64), optimize=True)
 
 
 def project_o(o, P_o):
     """y = einsum('bhv,hdv->bd') (last line of both incremental listings;
     note P_o is [h,d,v], model width before value width)."""
-    return np.einsum("bhv,hdv->bd", np.asarray(o, dtype=F64), np.asarray(P_o, dtype=F64))
+    return np.einsum("bhv,hdv->bd", np.asarray(o, dtype=F64), np.asarray(P_o, dtype=F64), optimize=True)
 
 
 def round_to_bf16(a):
@@ -200,7 +200,7 @@ def mqa_decode_weights(q, K, lens, scale=1.0):
         if L == 0:
             out.append(np.zeros((q.shape[1], 0)))
             continue
-        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L])
+        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L], optimize=True)
         out.append(softmax64(logits))
     return out
 
@@ -217,9 +217,9 @@ def mqa_decode(q, K, V, lens, scale=1.0):
         L = int(lens[i])
         if L == 0:
             continue
-        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L])
+        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L], optimize=True)
         weights = softmax64(logits)
-        o[i] = np.einsum("hm,mv->hv", weights, V[i, :L])
+        o[i] = np.einsum("hm,mv->hv", weights, V[i, :L], optimize=True)
     return o
 
 
@@ -234,9 +234,9 @@ def mha_decode(q, K, V, lens, scale=1.0):
         L = int(lens[i])
         if L == 0:
             continue
-        logits = scale * np.einsum("hk,hmk->hm", q[i], K[i, :, :L])
+        logits = scale * np.einsum("hk,hmk->hm", q[i], K[i, :, :L], optimize=True)
         weights = softmax64(logits)
-        o[i] = np.einsum("hm,hmv->hv", weights, V[i, :, :L])
+        o[i] = np.einsum("hm,hmv->hv", weights, V[i, :, :L], optimize=True)
     return o
 
 

@@ -1,0 +1,242 @@
+"""ctypes binding of libmqa_decode.so: same names as the C ABI (include/mqa.h),
+argument marshalling only.  torch is used for device memory and the current
+stream; every step of the path runs in the library's HIP kernels.  There is no
+fallback: if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libmqa_decode.so")
+
+MQA_F32, MQA_BF16 = 0, 1
+MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
+
+EXPORTS = [
+    "mqa_project_qkvo", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
+    "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
+    "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
+    "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
+]
+
+
+class mqa_tuning(ctypes.Structure):
+    _fields_ = [("splits", ctypes.c_int32), ("kernel", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class MqaError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__(f"{fn} failed: status {status} ({status_string(status)})")
+
+
+_lib = None
+
+
+def load_library(path: str = LIB_PATH):
+    """Loads the shared library (once).  Raises OSError if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise OSError(f"{path} not found: build it with `python -m paper_1911_02150_amd.build` "
+                      "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(path)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    tp = ctypes.POINTER(mqa_tuning)
+    dec = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    lib.mqa_project_qkvo.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.mqa_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+    lib.mqa_decode_step.argtypes = dec
+    lib.mha_decode_step.argtypes = dec
+    lib.mqa_decode_step_ex.argtypes = dec + [tp]
+    lib.mha_decode_step_ex.argtypes = dec + [tp]
+    lib.mqa_decode_partials.argtypes = dec + [tp]
+    lib.mqa_decode_combine.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp, tp]
+    lib.mqa_decode_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.mqa_decode_workspace_bytes.restype = sz
+    lib.mha_decode_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.mha_decode_workspace_bytes.restype = sz
+    lib.mqa_decode_num_splits.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp]
+    lib.mqa_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.mqa_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.mqa_status_string.argtypes = [ci]
+    lib.mqa_status_string.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_status_string"):
+            getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().mqa_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _tuning(tuning):
+    if tuning is None:
+        return None
+    if isinstance(tuning, mqa_tuning):
+        return ctypes.byref(tuning)
+    t = mqa_tuning(int(tuning.get("splits", 0)), int(tuning.get("kernel", 0)), int(tuning.get("flags", 0)))
+    return ctypes.byref(t)
+
+
+def _cache_dtype(K):
+    if K.dtype == torch.bfloat16:
+        return MQA_BF16
+    if K.dtype == torch.float32:
+        return MQA_F32
+    raise TypeError(f"cache dtype {K.dtype} not supported (float32 or bfloat16)")
+
+
+def _check(t, name, dtype=None):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+
+
+def mqa_decode_workspace_bytes(b, h, cap, v) -> int:
+    return int(load_library().mqa_decode_workspace_bytes(b, h, cap, v))
+
+
+def mha_decode_workspace_bytes(b, h, cap, v) -> int:
+    return int(load_library().mha_decode_workspace_bytes(b, h, cap, v))
+
+
+def mqa_decode_num_splits(b, h, cap, k, v, dt, multi_head=False, tuning=None) -> int:
+    return int(load_library().mqa_decode_num_splits(b, h, cap, k, v, dt, int(multi_head), _tuning(tuning)))
+
+
+def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tuning, with_tuning=True):
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
+    b, h, k = q.shape
+    cap, v = V.shape[-2], V.shape[-1]
+    want_k = (b, h, cap, k) if multi_head else (b, cap, k)
+    want_v = (b, h, cap, v) if multi_head else (b, cap, v)
+    if tuple(K.shape) != want_k or tuple(V.shape) != want_v or K.dtype != V.dtype or lens.numel() != b:
+        raise ValueError(f"shape mismatch: q {tuple(q.shape)} K {tuple(K.shape)} V {tuple(V.shape)} lens {tuple(lens.shape)}")
+    if o is None:
+        o = torch.empty((b, h, v), dtype=torch.float32, device=q.device)
+    _check(o, "o", torch.float32)
+    if tuple(o.shape) != (b, h, v):
+        raise ValueError("o must be [b,h,v]")
+    if workspace is None:
+        nbytes = mha_decode_workspace_bytes(b, h, cap, v) if multi_head else mqa_decode_workspace_bytes(b, h, cap, v)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    args = [_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K), float(scale),
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
+    if with_tuning:
+        args.append(_tuning(tuning))
+    rc = getattr(lib, fn_name)(*args)
+    if rc != 0:
+        raise MqaError(fn_name, rc)
+    return o
+
+
+def mqa_decode_step(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=None, tuning=None):
+    """q [b,h,k] f32, K [b,cap,k], V [b,cap,v] (f32 or bf16), lens [b] int32 -> o [b,h,v] f32."""
+    if tuning is None:
+        return _decode("mqa_decode_step", False, q, K, V, lens, o, scale, workspace, stream, None, False)
+    return _decode("mqa_decode_step_ex", False, q, K, V, lens, o, scale, workspace, stream, tuning)
+
+
+def mha_decode_step(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=None, tuning=None):
+    """q [b,h,k] f32, K [b,h,cap,k], V [b,h,cap,v], lens [b] int32 -> o [b,h,v] f32."""
+    if tuning is None:
+        return _decode("mha_decode_step", True, q, K, V, lens, o, scale, workspace, stream, None, False)
+    return _decode("mha_decode_step_ex", True, q, K, V, lens, o, scale, workspace, stream, tuning)
+
+
+def mqa_decode_partials(q, K, V, lens, o, workspace, scale=1.0, stream=None, tuning=None):
+    return _decode("mqa_decode_partials", False, q, K, V, lens, o, scale, workspace, stream, tuning)
+
+
+def mqa_decode_combine(lens, o, cap, k, cache_dtype, workspace, stream=None, tuning=None):
+    lib = load_library()
+    b, h, v = o.shape
+    rc = lib.mqa_decode_combine(_ptr(lens), _ptr(o), b, h, cap, k, v, cache_dtype, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream), _tuning(tuning))
+    if rc != 0:
+        raise MqaError("mqa_decode_combine", rc)
+    return o
+
+
+def mqa_append_kv(K, V, k_new, v_new, lens, stream=None):
+    """Appends k_new/v_new ([b,k]/[b,v] multi-query, [b,h,k]/[b,h,v] multi-head) in place; lens += 1."""
+    lib = load_library()
+    for t, n in ((K, "K"), (V, "V"), (k_new, "k_new"), (v_new, "v_new"), (lens, "lens")):
+        _check(t, n)
+    if k_new.dtype != torch.float32 or v_new.dtype != torch.float32 or lens.dtype != torch.int32:
+        raise TypeError("k_new/v_new must be float32 and lens int32")
+    b = K.shape[0]
+    h_kv = K.shape[1] if K.dim() == 4 else 1
+    cap, k, v = K.shape[-2], K.shape[-1], V.shape[-1]
+    if k_new.numel() != b * h_kv * k or v_new.numel() != b * h_kv * v or lens.numel() != b or V.shape[:-1] != K.shape[:-1]:
+        raise ValueError("shape mismatch in mqa_append_kv")
+    rc = lib.mqa_append_kv(_ptr(K), _ptr(V), _ptr(k_new), _ptr(v_new), _ptr(lens), b, h_kv, cap, k, v,
+                           _cache_dtype(K), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_append_kv", rc)
+
+
+def mqa_project_qkvo(mode, x, P, out=None, stream=None):
+    """mode Q/KV_MH: x [rows,d], P [h,d,kv] -> [rows,h,kv];  KV: P [d,kv] -> [rows,kv];
+    O: x [rows,h,kv], P [h,d,kv] -> [rows,d]."""
+    lib = load_library()
+    _check(x, "in", torch.float32), _check(P, "P", torch.float32)
+    rows = x.shape[0]
+    if mode == MQA_PROJ_KV:
+        d, kv = P.shape
+        h, oshape = 1, (rows, kv)
+        ok = x.shape == (rows, d)
+    elif mode in (MQA_PROJ_Q, MQA_PROJ_KV_MH):
+        h, d, kv = P.shape
+        oshape = (rows, h, kv)
+        ok = x.shape == (rows, d)
+    elif mode == MQA_PROJ_O:
+        h, d, kv = P.shape
+        oshape = (rows, d)
+        ok = x.shape == (rows, h, kv)
+    else:
+        raise ValueError("unknown projection mode")
+    if not ok:
+        raise ValueError(f"shape mismatch: in {tuple(x.shape)} P {tuple(P.shape)} mode {mode}")
+    if out is None:
+        out = torch.empty(oshape, dtype=torch.float32, device=x.device)
+    _check(out, "out", torch.float32)
+    rc = lib.mqa_project_qkvo(mode, _ptr(x), _ptr(P), _ptr(out), rows, d, h, kv, _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_project_qkvo", rc)
+    return out
+
+
+def mqa_stream_read(src, sink, stream=None):
+    lib = load_library()
+    rc = lib.mqa_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_stream_read", rc)
+
+
+def mqa_stream_copy(src, dst, stream=None):
+    lib = load_library()
+    rc = lib.mqa_stream_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_stream_copy", rc)

@@ -1,0 +1,232 @@
+// C-ABI layer: argument validation on the host, choice of the position split
+// and of the kernel, launches.  Validation happens before any HIP call, so the
+// error paths run on a machine without a GPU.
+#include "../../include/mqa.h"
+#include "common.hpp"
+
+using namespace mqa;
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+constexpr int kTargetBlocks = 1024;   // workgroups wanted in flight (256 CUs x 2 x 2)
+
+struct Plan {
+  bool use_mfma;
+  int S, chunk, HG;
+};
+
+// Split of the position axis.  Every range is a multiple of 32 positions; a
+// range is at least 128 (MFMA: one tile per wave) or 256 (generic) positions.
+int plan_decode(int nseq, int G, int cap, int k, int v, int is_bf16, const Tuning& tn, Plan* pl) {
+  const bool ok = mfma_shape_ok(G, k, v, is_bf16);
+  if (tn.kernel == 2 && !ok) return MQA_ERR_SHAPE;
+  pl->use_mfma = ok && tn.kernel != 1;
+  pl->HG = 1;
+  if (pl->use_mfma) pl->HG = (G + 16 * mfma_head_blocks(G) - 1) / (16 * mfma_head_blocks(G));
+  const int min_chunk = pl->use_mfma ? 128 : 256;
+  int max_s = (cap + min_chunk - 1) / min_chunk;
+  if (max_s > kMaxSplits) max_s = kMaxSplits;
+  if (max_s < 1) max_s = 1;
+  int S;
+  if (tn.splits > 0) {
+    S = tn.splits > kMaxSplits ? kMaxSplits : tn.splits;
+    const int by_len = (cap + 31) / 32;
+    if (S > by_len) S = by_len;
+  } else {
+    const long long groups = (long long)nseq * pl->HG;
+    S = (int)((kTargetBlocks + groups - 1) / groups);
+    if (S > max_s) S = max_s;
+  }
+  if (S < 1) S = 1;
+  int chunk = (cap + S - 1) / S;
+  chunk = (chunk + 31) & ~31;
+  pl->chunk = chunk;
+  pl->S = (cap + chunk - 1) / chunk;
+  return MQA_OK;
+}
+
+size_t partial_bytes(long long nseq, int S, int G, int v) {
+  return (size_t)nseq * S * G * (v + 2) * sizeof(float);
+}
+
+int check_decode_args(const float* q, const void* K, const void* V, const int32_t* lens, const float* o,
+                      int b, int h, int cap, int k, int v, int dt, bool need_qkv) {
+  if (!lens || !o || (need_qkv && (!q || !K || !V))) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || h <= 0 || cap <= 0 || k <= 0 || v <= 0) return MQA_ERR_SHAPE;
+  if ((k & 7) || (v & 7) || k > 256 || v > 256) return MQA_ERR_SHAPE;
+  if ((long long)b * h > (1ll << 24) || cap > (1 << 24)) return MQA_ERR_SHAPE;
+  if (misaligned(o) || misaligned(lens) || (need_qkv && (misaligned(q) || misaligned(K) || misaligned(V))))
+    return MQA_ERR_ALIGN;
+  return MQA_OK;
+}
+
+// phase bit 0: partial pass, bit 1: combine pass
+int decode_impl(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                int b, int h, int cap, int k, int v, int dt, float scale,
+                void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning,
+                bool multi_head, int phase) {
+  int rc = check_decode_args(q, K, V, lens, o, b, h, cap, k, v, dt, (phase & 1) != 0);
+  if (rc) return rc;
+  Tuning tn;
+  if (tuning) {
+    tn.splits = tuning->splits;
+    tn.kernel = tuning->kernel;
+    tn.flags = tuning->flags;
+  }
+  const int nseq = multi_head ? b * h : b;
+  const int G = multi_head ? 1 : h;
+  Plan pl;
+  rc = plan_decode(nseq, G, cap, k, v, dt == MQA_BF16, tn, &pl);
+  if (rc) return rc;
+  if (pl.S > 1) {
+    if (!workspace || workspace_bytes < partial_bytes(nseq, pl.S, G, v)) return MQA_ERR_WORKSPACE;
+    if (misaligned(workspace)) return MQA_ERR_ALIGN;
+  }
+  DecodeParams p;
+  p.q = q; p.K = K; p.V = V; p.lens = lens; p.o = o;
+  p.part_o = static_cast<float*>(workspace);
+  p.part_m = p.part_o ? p.part_o + (size_t)nseq * pl.S * G * v : nullptr;
+  p.part_l = p.part_m ? p.part_m + (size_t)nseq * pl.S * G : nullptr;
+  p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
+  p.k = k; p.v = v; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
+  p.qscale = scale * kLog2e;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (phase & 1) {
+    hipError_t e = pl.use_mfma ? launch_decode_mfma(p, tn.flags, st)
+                               : launch_decode_generic(p, dt == MQA_BF16, st);
+    if (e != hipSuccess) return MQA_ERR_LAUNCH;
+  }
+  if ((phase & 2) && pl.S > 1) {
+    if (launch_combine(p, st) != hipSuccess) return MQA_ERR_LAUNCH;
+  }
+  return MQA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mqa_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                    int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, false, 3);
+}
+
+int mha_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                    int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, true, 3);
+}
+
+int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                       int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning) {
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     tuning, false, 3);
+}
+
+int mha_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                       int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning) {
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     tuning, true, 3);
+}
+
+int mqa_decode_partials(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                        int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                        void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning) {
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     tuning, false, 1);
+}
+
+int mqa_decode_combine(const int32_t* lens, float* o, int b, int h, int cap, int k, int v, mqa_dtype dt,
+                       void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning) {
+  return decode_impl(nullptr, nullptr, nullptr, lens, o, b, h, cap, k, v, (int)dt, 1.0f, workspace,
+                     workspace_bytes, stream, tuning, false, 2);
+}
+
+size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v) {
+  if (b <= 0 || h <= 0 || cap <= 0 || v <= 0) return 0;
+  int S = (cap + 31) / 32;
+  if (S > kMaxSplits) S = kMaxSplits;
+  return partial_bytes(b, S, h, v);
+}
+
+size_t mha_decode_workspace_bytes(int b, int h, int cap, int v) {
+  return mqa_decode_workspace_bytes(b, h, cap, v);   // b*h groups of one head: same element count
+}
+
+int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head,
+                          const mqa_tuning* tuning) {
+  if (b <= 0 || h <= 0 || cap <= 0 || k <= 0 || v <= 0) return -MQA_ERR_SHAPE;
+  Tuning tn;
+  if (tuning) {
+    tn.splits = tuning->splits;
+    tn.kernel = tuning->kernel;
+    tn.flags = tuning->flags;
+  }
+  Plan pl;
+  const int rc = plan_decode(multi_head ? b * h : b, multi_head ? 1 : h, cap, k, v, dt == MQA_BF16, tn, &pl);
+  return rc ? -rc : pl.S;
+}
+
+int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
+                  int b, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream) {
+  if (!K || !V || !k_new || !v_new || !lens) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || h_kv <= 0 || cap <= 0 || k <= 0 || v <= 0) return MQA_ERR_SHAPE;
+  if ((k & 7) || (v & 7)) return MQA_ERR_SHAPE;
+  if (misaligned(K) || misaligned(V) || misaligned(k_new) || misaligned(v_new) || misaligned(lens))
+    return MQA_ERR_ALIGN;
+  if (launch_append(K, V, k_new, v_new, lens, b, h_kv, cap, k, v, dt == MQA_BF16,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
+int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,
+                     int rows, int d, int h, int kv, void* stream) {
+  if (!in || !P || !out) return MQA_ERR_NULL;
+  if ((int)mode < 0 || (int)mode > 3) return MQA_ERR_DTYPE;
+  if (mode == MQA_PROJ_KV) h = 1;
+  if (rows <= 0 || d <= 0 || h <= 0 || kv <= 0) return MQA_ERR_SHAPE;
+  if ((d & 7) || (kv & 7)) return MQA_ERR_SHAPE;
+  if (misaligned(in) || misaligned(P) || misaligned(out)) return MQA_ERR_ALIGN;
+  if (launch_project((int)mode, in, P, out, rows, d, h, kv, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
+int mqa_stream_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (!src || !sink) return MQA_ERR_NULL;
+  if (bytes == 0 || (bytes & 15)) return MQA_ERR_SHAPE;
+  if (misaligned(src)) return MQA_ERR_ALIGN;
+  return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst) return MQA_ERR_NULL;
+  if (bytes == 0 || (bytes & 15)) return MQA_ERR_SHAPE;
+  if (misaligned(src) || misaligned(dst)) return MQA_ERR_ALIGN;
+  return launch_stream_copy(src, dst, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+const char* mqa_status_string(int status) {
+  switch (status) {
+    case MQA_OK: return "ok";
+    case MQA_ERR_NULL: return "null pointer";
+    case MQA_ERR_SHAPE: return "unsupported or non-positive size";
+    case MQA_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case MQA_ERR_WORKSPACE: return "workspace missing or too small";
+    case MQA_ERR_DTYPE: return "unknown dtype or mode";
+    case MQA_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

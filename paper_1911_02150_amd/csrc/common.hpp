@@ -1,0 +1,81 @@
+// Shared declarations of the gfx950 decode library: kernel parameter blocks and
+// the host-side launchers each .hip file exports to the C-ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mqa {
+
+constexpr int kMaxSplits = 64;          // upper bound on position ranges per sequence
+constexpr float kLog2e = 1.4426950408889634f;
+
+// One decode launch.  "Sequences" here are KV groups: a multi-query call has
+// nseq = b groups of G = h heads; a multi-head call has nseq = b*h groups of
+// G = 1 head, and lens is indexed by seq / lens_div (lens_div = h).
+struct DecodeParams {
+  const float* q;        // [nseq, G, k]
+  const void* K;         // [nseq, cap, k]
+  const void* V;         // [nseq, cap, v]
+  const int32_t* lens;   // [nseq / lens_div]
+  float* o;              // [nseq, G, v]
+  float* part_o;         // [nseq, S, G, v]  un-normalised partial outputs
+  float* part_m;         // [nseq, S, G]     running maxima (log2 domain)
+  float* part_l;         // [nseq, S, G]     sums of 2^(logit - max)
+  int nseq, G, cap, lens_div;
+  int k, v;
+  int chunk;             // positions per range (multiple of 32)
+  int S;                 // ranges per sequence
+  int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
+  float qscale;          // scale * log2(e): logits are kept in the log2 domain
+};
+
+struct Tuning {
+  int splits = 0;
+  int kernel = 0;
+  int flags = 0;
+};
+
+// decode_mfma.hip: bf16 cache, k = v = 128.  hb = head blocks of 16 (1, 2 or 4).
+bool mfma_shape_ok(int G, int k, int v, int is_bf16);
+int mfma_head_blocks(int G);
+hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
+
+// decode_generic.hip: any k, v <= 256, float32 or bf16 cache.
+hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t st);
+
+// small_kernels.hip
+hipError_t launch_combine(const DecodeParams& p, hipStream_t st);
+hipError_t launch_append(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
+                         int b, int h_kv, int cap, int k, int v, int is_bf16, hipStream_t st);
+hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t st);
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+
+// project.hip
+hipError_t launch_project(int mode, const float* in, const float* P, float* out,
+                          int rows, int d, int h, int kv, hipStream_t st);
+
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+
+// float32 -> bf16 bits, round to nearest even; NaN stays NaN (quiet).
+__device__ __forceinline__ uint32_t float_to_bf16_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+}  // namespace mqa

@@ -1,0 +1,357 @@
+// Decode attention for a bf16 cache with k = v = 128 on gfx950 matrix cores.
+//
+// Computes, per KV group ("sequence") and per position range, the three lines
+// logits / weights / o of the paper's incremental listings (Section 3 for
+// multi-query, Section 2.4 for multi-head with one head per group):
+//   logits[j,p] = sum_c q[j,c] K[p,c];  weights = softmax_p;  o[j,:] = sum_p weights[j,p] V[p,:]
+//
+// Work decomposition
+//   grid  = nseq * S * HG workgroups (sequence, position range, group of 16*HB heads)
+//   block = NW independent wavefronts; wave w takes the 32-position tiles
+//           w, w+NW, ... of the range, so the block streams its range front to back.
+//   Each wave keeps, for all 16*HB heads, a running maximum, a running sum and
+//   the un-normalised output O^T [128 x 16*HB] in MFMA accumulators.  At the end
+//   the NW partial states are merged through LDS and written either as the
+//   final o (S = 1) or as one partial state per range for the combine pass.
+//
+// Register-direct operands (no LDS on the K/V path)
+//   v_mfma_f32_16x16x32_bf16: D[16x16] += A[16x32] B[32x16]; lane l = i + 16 g
+//   holds A[i][slots (g,0..7)], B[slots (g,0..7)][i] and D[4g+r][i], r = 0..3.
+//   The contraction does not care which k index a slot denotes as long as A and
+//   B agree, so slots are assigned to suit the memory layout:
+//   * logits^T tile = K_tile[16 pos x 128] . q^T[128 x 16 heads], 4 MFMA steps.
+//     Lane (i,g) loads 4 x 16 B of ONE K row; step s uses 16-byte column chunk
+//     4s+g of the row for both K and q.  MFMA row i stands for position
+//     p0 + 16u + 4(i%4) + i/4, which makes the result lane (head, g) hold
+//     positions p0 + 16u + 4r + g.
+//   * O^T[16 cols x 16 heads] += V^T[16 cols x 32 pos] . P^T[32 pos x 16 heads].
+//     The 8 logits a lane owns (2 sub-tiles x 4) are exactly its 8 B-operand
+//     slots, so the weights feed the second MFMA without leaving the lane.
+//     For the A operand lane (c,g) loads 16 B (8 columns 8c..8c+7) of the 8 rows
+//     p0 + 4e + g (each load instruction covers 4 whole rows = 1 KiB contiguous)
+//     and transposes the 8x8 block inside the lane with 32 byte-permutes; MFMA j
+//     then uses column 8c+j, and D_j row i stands for output column 8i+j.
+//   q (fp32) and the weights are split into bf16 hi + lo terms (two MFMAs) so
+//   that only K/V storage, not the arithmetic, is reduced precision.
+#include "common.hpp"
+
+namespace mqa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+namespace {
+
+constexpr int kD = 128;            // k = v = 128
+constexpr int kRowU4 = kD * 2 / 16;  // 16-byte words per cache row (16)
+constexpr int kOPitch = kD + 4;    // LDS row pitch (floats) of the merge buffers
+
+__device__ __forceinline__ floatx4 mfma16(const u32x4& a, const u32x4& b, const floatx4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ u32x4 ld16(const u32x4* p) { return *p; }
+
+// hi/lo bf16 split of 8 floats -> two packed operands
+__device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    uint32_t h0 = float_to_bf16_rne(x[2 * d]), h1 = float_to_bf16_rne(x[2 * d + 1]);
+    float r0 = x[2 * d] - bf16_bits_to_float(h0), r1 = x[2 * d + 1] - bf16_bits_to_float(h1);
+    hi[d] = h0 | (h1 << 16);
+    lo[d] = float_to_bf16_rne(r0) | (float_to_bf16_rne(r1) << 16);
+  }
+}
+
+template <int HB, int NW, bool QSPLIT, bool PSPLIT>
+__global__ __launch_bounds__(NW * 64, (HB <= 2 ? 2 : 1))
+void decode_mfma_kernel(DecodeParams p) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, g = lane >> 4;
+  constexpr int NT = NW * 64;
+  constexpr int NH = 16 * HB;                 // heads handled by this block
+
+  // workgroup -> (sequence, range, head group); consecutive work items share an XCD
+  const int nb = gridDim.x, bid = blockIdx.x;
+  const int wid = ((nb & 7) == 0) ? (bid & 7) * (nb >> 3) + (bid >> 3) : bid;
+  const int hg = wid % p.HG;
+  const int srange = (wid / p.HG) % p.S;
+  const int seq = wid / (p.HG * p.S);
+  const int head0 = hg * NH;
+
+  int L = p.lens[seq / p.lens_div];
+  L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
+  const int begin = srange * p.chunk;
+  const int end = min(begin + p.chunk, L);
+  if (end <= begin) {
+    if (p.S == 1) {           // empty sequence: zero output rows
+      for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
+        int hl = idx / (kD / 4), c4 = idx % (kD / 4);
+        if (head0 + hl < p.G)
+          reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head0 + hl) * kD)[c4] =
+              make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+    return;                   // ranges past the length write nothing; the combine skips them
+  }
+  const int ntiles = (end - begin + 31) >> 5;
+
+  // ---- q -> LDS as MFMA B operands: qs[(hb*4 + s)*64 + lane] (hi), then lo
+  u32x4* qs = reinterpret_cast<u32x4*>(smem_raw);
+  constexpr int QOPS = HB * 4 * 64;
+  for (int idx = tid; idx < NH * 16; idx += NT) {
+    const int hl = idx >> 4, c = idx & 15;          // head in block, 16-byte chunk of the row
+    const int s4 = c >> 2, gg = c & 3;              // chunk c = 4s + g
+    float x[8];
+    if (head0 + hl < p.G) {
+      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * p.G + head0 + hl) * kD + c * 8);
+      float4 a = src[0], b = src[1];
+      x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] *= p.qscale;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = 0.f;
+    }
+    u32x4 hi, lo;
+    split8(x, hi, lo);
+    const int slot = (((hl >> 4) * 4 + s4) * 64) + (hl & 15) + 16 * gg;
+    qs[slot] = hi;
+    qs[QOPS + slot] = lo;
+  }
+  __syncthreads();
+
+  floatx4 acc[HB][8];
+  float m_run[HB], l_run[HB];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    m_run[hb] = -INFINITY;
+    l_run[hb] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[hb][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const u32x4* Kbase = reinterpret_cast<const u32x4*>(p.K) + (size_t)seq * p.cap * kRowU4;
+  const u32x4* Vbase = reinterpret_cast<const u32x4*>(p.V) + (size_t)seq * p.cap * kRowU4;
+  const int krow_in_tile = 4 * (i16 & 3) + (i16 >> 2);
+  const int last = end - 1;
+
+  u32x4 kr[2][4], vr[8];
+  auto load_k = [&](int t) {
+    const int p0 = begin + 32 * t;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = min(p0 + 16 * u + krow_in_tile, last);
+      const u32x4* src = Kbase + (size_t)row * kRowU4 + g;
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) kr[u][s4] = ld16(src + 4 * s4);
+    }
+  };
+  auto load_v = [&](int t) {
+    const int p0 = begin + 32 * t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int row = min(p0 + 4 * e + g, last);
+      vr[e] = ld16(Vbase + (size_t)row * kRowU4 + i16);
+    }
+  };
+
+  int t = wave;
+  if (t < ntiles) {
+    load_k(t);
+    load_v(t);
+  }
+  for (; t < ntiles; t += NW) {
+    const int p0 = begin + 32 * t;
+    const int tn = min(t + NW, ntiles - 1);
+
+    // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
+    floatx4 sc[2][HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      sc[0][hb] = floatx4{0.f, 0.f, 0.f, 0.f};
+      sc[1][hb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const u32x4 qh = qs[(hb * 4 + s4) * 64 + lane];
+        sc[0][hb] = mfma16(kr[0][s4], qh, sc[0][hb]);
+        sc[1][hb] = mfma16(kr[1][s4], qh, sc[1][hb]);
+        if (QSPLIT) {
+          const u32x4 ql = qs[QOPS + (hb * 4 + s4) * 64 + lane];
+          sc[0][hb] = mfma16(kr[0][s4], ql, sc[0][hb]);
+          sc[1][hb] = mfma16(kr[1][s4], ql, sc[1][hb]);
+        }
+      }
+    }
+    load_k(tn);                 // K registers are free: fetch the wave's next tile
+
+    if (p0 + 32 > end) {        // ragged tail of the range
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (p0 + 16 * u + 4 * r + g >= end) {
+#pragma unroll
+            for (int hb = 0; hb < HB; ++hb) sc[u][hb][r] = -INFINITY;
+          }
+    }
+
+    // ---- online softmax per head block; weights packed as MFMA B operands
+    u32x4 phi[HB], plo[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+      float mx = fmaxf(fmaxf(fmaxf(sc[0][hb][0], sc[0][hb][1]), fmaxf(sc[0][hb][2], sc[0][hb][3])),
+                       fmaxf(fmaxf(sc[1][hb][0], sc[1][hb][1]), fmaxf(sc[1][hb][2], sc[1][hb][3])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = fmaxf(m_run[hb], mx);
+      if (__any(mnew > m_run[hb])) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - mnew);
+        l_run[hb] *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[hb][j] *= alpha;
+        m_run[hb] = mnew;
+      }
+      float pe[8];
+      float sum = 0.f;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          pe[4 * u + r] = __builtin_amdgcn_exp2f(sc[u][hb][r] - m_run[hb]);
+          sum += pe[4 * u + r];
+        }
+      l_run[hb] += sum;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const uint32_t b0 = __float_as_uint(pe[2 * d]), b1 = __float_as_uint(pe[2 * d + 1]);
+        phi[hb][d] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);     // truncated hi halves
+        if (PSPLIT) {
+          const float r0 = pe[2 * d] - __uint_as_float(b0 & 0xffff0000u);
+          const float r1 = pe[2 * d + 1] - __uint_as_float(b1 & 0xffff0000u);
+          plo[hb][d] = float_to_bf16_rne(r0) | (float_to_bf16_rne(r1) << 16);
+        }
+      }
+    }
+
+    // ---- O^T += V^T . P^T, V transposed 8x8 inside the lane
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const int j = 2 * w + par;
+        u32x4 a;
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          a[x] = __builtin_amdgcn_perm(vr[2 * x + 1][w], vr[2 * x][w], par ? 0x07060302u : 0x05040100u);
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+          acc[hb][j] = mfma16(a, phi[hb], acc[hb][j]);
+          if (PSPLIT) acc[hb][j] = mfma16(a, plo[hb], acc[hb][j]);
+        }
+      }
+    }
+    load_v(tn);
+  }
+
+  // ---- merge the NW wave states through LDS (re-using the q region)
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    l_run[hb] += __shfl_xor(l_run[hb], 16);
+    l_run[hb] += __shfl_xor(l_run[hb], 32);
+  }
+  __syncthreads();
+  float* so = reinterpret_cast<float*>(smem_raw);           // [NW][NH][kOPitch]
+  float* sm = so + NW * NH * kOPitch;                       // [NW][NH]
+  float* sl = sm + NW * NH;                                 // [NW][NH]
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    float* row = so + ((size_t)wave * NH + 16 * hb + i16) * kOPitch;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float4 lo4 = make_float4(acc[hb][0][r], acc[hb][1][r], acc[hb][2][r], acc[hb][3][r]);
+      float4 hi4 = make_float4(acc[hb][4][r], acc[hb][5][r], acc[hb][6][r], acc[hb][7][r]);
+      float4* dst = reinterpret_cast<float4*>(row + 8 * (4 * g + r));
+      dst[0] = lo4;
+      dst[1] = hi4;
+    }
+    if (g == 0) {
+      sm[wave * NH + 16 * hb + i16] = m_run[hb];
+      sl[wave * NH + 16 * hb + i16] = l_run[hb];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
+    const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
+    if (head0 + hl >= p.G) continue;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, sm[w * NH + hl]);
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float f = __builtin_amdgcn_exp2f(sm[w * NH + hl] - M);   // wave 0 always has a tile: M finite
+      const float4 x = reinterpret_cast<const float4*>(so + ((size_t)w * NH + hl) * kOPitch)[c4];
+      a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
+      lsum += f * sl[w * NH + hl];
+    }
+    const int head = head0 + hl;
+    if (p.S == 1) {
+      const float inv = 1.0f / lsum;
+      a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+      reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * kD)[c4] = a;
+    } else {
+      const size_t pidx = ((size_t)seq * p.S + srange) * p.G + head;
+      reinterpret_cast<float4*>(p.part_o + pidx * kD)[c4] = a;
+      if (c4 == 0) {
+        p.part_m[pidx] = M;
+        p.part_l[pidx] = lsum;
+      }
+    }
+  }
+}
+
+template <int HB, int NW>
+hipError_t launch_hb(const DecodeParams& p, int flags, hipStream_t st) {
+  const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
+  const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 2 * NW * 16 * HB) * sizeof(float);
+  const size_t lds = q_bytes > merge_bytes ? q_bytes : merge_bytes;
+  const dim3 grid((unsigned)((size_t)p.nseq * p.S * p.HG)), block(NW * 64);
+  void (*kern)(DecodeParams);
+  switch (flags & 3) {
+    case 0: kern = decode_mfma_kernel<HB, NW, true, true>; break;
+    case 1: kern = decode_mfma_kernel<HB, NW, false, true>; break;
+    case 2: kern = decode_mfma_kernel<HB, NW, true, false>; break;
+    default: kern = decode_mfma_kernel<HB, NW, false, false>; break;
+  }
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, grid, block, lds, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_shape_ok(int G, int k, int v, int is_bf16) {
+  (void)G;
+  return is_bf16 && k == kD && v == kD;
+}
+
+int mfma_head_blocks(int G) { return G <= 16 ? 1 : (G <= 32 ? 2 : 4); }
+
+hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
+  switch (mfma_head_blocks(p.G)) {
+    case 1: return launch_hb<1, 4>(p, flags, st);
+    case 2: return launch_hb<2, 4>(p, flags, st);
+    default: return launch_hb<4, 4>(p, flags, st);
+  }
+}
+
+}  // namespace mqa

@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every function include/mqa.h declares, and rejects bad arguments before
+touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1911_02150_amd", "libmqa_decode.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="library not built (run __graft_entry__.build())")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mqa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(m[qh]a_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    from paper_1911_02150_amd import binding
+    lib = ctypes.CDLL(LIB)
+    names = declared_functions()
+    assert {"mqa_append_kv", "mqa_decode_step", "mha_decode_step", "mqa_project_qkvo"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mqa.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    from paper_1911_02150_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    with pytest.raises(OSError, match="no CPU or PyTorch fallback"):
+        binding.load_library(str(tmp_path / "absent.so"))
+
+
+def test_host_side_sizes_and_plan():
+    import paper_1911_02150_amd as m
+    assert m.mqa_decode_workspace_bytes(64, 32, 8192, 128) == 64 * 64 * 32 * 130 * 4
+    assert m.mqa_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4
+    assert m.mqa_decode_workspace_bytes(0, 3, 40, 8) == 0
+    assert m.mqa_decode_num_splits(128, 8, 128, 128, 128, m.MQA_BF16) == 1          # short caches: one range
+    assert m.mqa_decode_num_splits(64, 32, 8192, 128, 128, m.MQA_BF16) > 1          # long cache: split
+    assert m.mqa_decode_num_splits(64, 32, 8192, 128, 128, m.MQA_BF16, tuning=dict(splits=5)) == 5
+    assert m.mqa_decode_num_splits(1, 8, 64, 128, 128, m.MQA_BF16, tuning=dict(splits=9)) == 2   # at most cap/32
+    assert m.mqa_decode_num_splits(4, 8, 64, 64, 64, m.MQA_BF16, tuning=dict(kernel=2)) == -2    # MFMA kernel needs k=v=128
+    assert m.status_string(0) == "ok" and "workspace" in m.status_string(4)
+
+
+def test_argument_validation_without_gpu():
+    lib = ctypes.CDLL(LIB)
+    vp = ctypes.c_void_p
+    A = vp(0x10000)          # non-null, aligned; never dereferenced on these paths
+    U = vp(0x10004)          # misaligned
+    dec = lib.mqa_decode_step
+    dec.argtypes = [vp] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, vp, ctypes.c_size_t, vp]
+    ok = dict(b=2, h=4, cap=4096, k=128, v=128, dt=1)
+
+    def call(q=A, K=A, V=A, lens=A, o=A, ws=A, wsb=1 << 30, **kw):
+        a = dict(ok, **kw)
+        return dec(q, K, V, lens, o, a["b"], a["h"], a["cap"], a["k"], a["v"], a["dt"], 1.0, ws, wsb, None)
+
+    assert call(q=None) == 1 and call(lens=None) == 1 and call(o=None) == 1
+    assert call(b=0) == 2 and call(h=-1) == 2 and call(k=12) == 2 and call(v=264) == 2 and call(cap=0) == 2
+    assert call(K=U) == 3 and call(o=U) == 3
+    assert call(dt=7) == 5
+    assert call(ws=None) == 4 and call(wsb=16) == 4            # this shape needs a split, hence a workspace
+    mha = lib.mha_decode_step
+    mha.argtypes = dec.argtypes
+    assert mha(A, A, None, A, A, 2, 4, 64, 128, 128, 1, 1.0, A, 1 << 20, None) == 1
+
+    app = lib.mqa_append_kv
+    app.argtypes = [vp] * 5 + [ctypes.c_int] * 6 + [vp]
+    assert app(A, A, A, None, A, 2, 1, 8, 128, 128, 1, None) == 1
+    assert app(A, A, A, A, A, 2, 0, 8, 128, 128, 1, None) == 2
+    assert app(A, A, A, A, A, 2, 1, 8, 100, 128, 1, None) == 2
+    assert app(A, U, A, A, A, 2, 1, 8, 128, 128, 1, None) == 3
+    assert app(A, A, A, A, A, 2, 1, 8, 128, 128, 3, None) == 5
+
+    prj = lib.mqa_project_qkvo
+    prj.argtypes = [ctypes.c_int, vp, vp, vp] + [ctypes.c_int] * 4 + [vp]
+    assert prj(0, None, A, A, 4, 64, 2, 16, None) == 1
+    assert prj(9, A, A, A, 4, 64, 2, 16, None) == 5
+    assert prj(0, A, A, A, 4, 60, 2, 16, None) == 2
+    assert prj(3, A, A, U, 4, 64, 2, 16, None) == 3
+
+    rd = lib.mqa_stream_read
+    rd.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    assert rd(A, 24, A, None) == 2 and rd(None, 32, A, None) == 1

@@ -1,0 +1,289 @@
+"""Parity of the HIP path (through the C ABI) with the float64 oracle, element
+by element on the same seeded inputs.
+
+Tolerances (the build's stated bar): float32 cache: max |g - r| <= 1e-5;
+bf16 cache with float32 accumulation: max |g - r| <= 2e-2 and
+max |g - r| / max |r| <= 1e-2, per tensor.  The cache values are rounded to
+bf16 on the host and the same rounded values go to both sides, so the
+comparison measures the GPU's arithmetic, not the quantisation.
+"""
+import numpy as np
+import pytest
+import torch
+
+import mqa_inputs as mi
+from oracle import mqa_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_1911_02150_amd as lib
+    lib.load_library()
+    return lib
+
+
+def to_dev_cache(a):
+    if a.dtype == np.uint16:
+        return mi.bits_to_torch_bf16(a).to(DEV)
+    return torch.from_numpy(a).to(DEV)
+
+
+def check(got, ref, cache, what=""):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = float(np.max(np.abs(got - ref))) if ref.size else 0.0
+    scale = float(np.max(np.abs(ref))) if ref.size else 1.0
+    if cache == "f32":
+        assert err <= 1e-5, f"{what}: max abs err {err:.3e} > 1e-5"
+    else:
+        assert err <= 2e-2, f"{what}: max abs err {err:.3e} > 2e-2"
+        assert err <= 1e-2 * max(scale, 1e-30), f"{what}: rel err {err / scale:.3e} > 1e-2"
+    return err
+
+
+def run_case(m, c, multi_head, scale=1.0, tuning=None):
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.from_numpy(c["lens"]).to(DEV)
+    fn = m.mha_decode_step if multi_head else m.mqa_decode_step
+    o = fn(q, K, V, lens, scale=scale, tuning=tuning)
+    torch.cuda.synchronize()
+    ofn = orc.mha_decode if multi_head else orc.mqa_decode
+    ref = ofn(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"], scale)
+    return o, ref
+
+
+# ----------------------------------------------------------------- MFMA kernel, bf16, k = v = 128
+MFMA_CASES = [
+    # (seed, b, h, cap, lens, splits)
+    (1, 3, 8, 128, "full", 0),
+    (2, 2, 32, 300, "ragged", 0),          # several tiles + ragged tail
+    (3, 5, 1, 97, "ragged", 0),
+    (4, 2, 20, 1000, "ragged", 3),         # h not a multiple of 16, forced split
+    (5, 3, 64, 515, "with_zero", 2),       # four head blocks, empty sequences
+    (6, 1, 72, 260, "full", 1),            # more than 64 heads: two head groups
+    (7, 4, 16, 2048, "ragged", 7),
+    (8, 2, 32, 4100, "full", 0),           # heuristics choose the split
+    (9, 6, 8, 33, [1, 2, 31, 32, 33, 17], 0),
+    (10, 2, 40, 64, "with_zero", 2),
+]
+
+
+@pytest.mark.parametrize("seed,b,h,cap,lens,splits", MFMA_CASES)
+def test_mqa_decode_bf16(m, seed, b, h, cap, lens, splits):
+    c = mi.random_case(seed, b, h, cap, 128, 128, cache="bf16", lens=lens)
+    tuning = dict(splits=splits, kernel=2) if splits else dict(kernel=2)
+    o, ref = run_case(m, c, False, tuning=tuning)
+    err = check(o, ref, "bf16", f"mqa bf16 seed {seed}")
+    print(f"mqa bf16 case {seed}: max abs err {err:.2e}")
+
+
+@pytest.mark.parametrize("flags", [1, 2, 3])
+def test_mqa_decode_bf16_reduced_terms(m, flags):
+    """The faster single-term variants still meet the bf16 tolerance on the bandwidth-probe distribution."""
+    c = mi.random_case(40 + flags, 2, 32, 1024, 128, 128, cache="bf16", lens="ragged")
+    o, ref = run_case(m, c, False, tuning=dict(kernel=2, flags=flags, splits=2))
+    check(o, ref, "bf16", f"flags {flags}")
+
+
+def test_mqa_decode_bf16_large_logits_and_scale(m):
+    # un-scaled queries (logits of std ~ sqrt(128)) and an explicit scale factor
+    c = mi.random_case(11, 3, 8, 200, 128, 128, cache="bf16", lens="ragged", q_std=1.0)
+    o, ref = run_case(m, c, False)
+    check(o, ref, "bf16", "unit-variance q")
+    o, ref = run_case(m, c, False, scale=0.25)
+    check(o, ref, "bf16", "scale 0.25")
+
+
+@pytest.mark.parametrize("seed,b,h,cap,lens,splits", [
+    (21, 2, 8, 128, "full", 0), (22, 2, 5, 300, "ragged", 2), (23, 3, 3, 70, "with_zero", 0),
+])
+def test_mha_decode_bf16(m, seed, b, h, cap, lens, splits):
+    c = mi.random_case(seed, b, h, cap, 128, 128, cache="bf16", lens=lens, multi_head=True)
+    o, ref = run_case(m, c, True, tuning=dict(splits=splits) if splits else None)
+    check(o, ref, "bf16", f"mha bf16 seed {seed}")
+
+
+def test_mqa_equals_mha_on_shared_kv_gpu(m):
+    """Section 3: multi-query is multi-head with every head reading the same K/V."""
+    c = mi.random_case(24, 2, 6, 150, 128, 128, cache="bf16", lens="ragged")
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.from_numpy(c["lens"]).to(DEV)
+    o1 = m.mqa_decode_step(q, K, V, lens)
+    Kh = K[:, None].expand(2, 6, 150, 128).contiguous()
+    Vh = V[:, None].expand(2, 6, 150, 128).contiguous()
+    o2 = m.mha_decode_step(q, Kh, Vh, lens)
+    assert float((o1 - o2).abs().max()) <= 1e-5
+
+
+# ----------------------------------------------------------------- generic kernel
+GENERIC_CASES = [
+    # (seed, b, h, cap, k, v, cache, lens, splits, multi_head)
+    (31, 1, 8, 128, 128, 128, "f32", "full", 0, False),
+    (32, 3, 5, 200, 64, 32, "f32", "ragged", 0, False),
+    (33, 2, 11, 700, 40, 72, "f32", "with_zero", 3, False),
+    (34, 2, 9, 130, 256, 256, "f32", "ragged", 0, False),
+    (35, 2, 4, 90, 64, 64, "bf16", "ragged", 0, False),
+    (36, 2, 3, 300, 128, 128, "f32", "ragged", 2, True),
+    (37, 2, 3, 65, 16, 8, "bf16", "full", 0, True),
+]
+
+
+@pytest.mark.parametrize("seed,b,h,cap,k,v,cache,lens,splits,mh", GENERIC_CASES)
+def test_decode_generic(m, seed, b, h, cap, k, v, cache, lens, splits, mh):
+    c = mi.random_case(seed, b, h, cap, k, v, cache=cache, lens=lens, multi_head=mh)
+    o, ref = run_case(m, c, mh, tuning=dict(splits=splits, kernel=1))
+    check(o, ref, cache, f"generic seed {seed}")
+
+
+def test_generic_matches_mfma_kernel(m):
+    c = mi.random_case(38, 2, 8, 400, 128, 128, cache="bf16", lens="ragged")
+    o1, ref = run_case(m, c, False, tuning=dict(kernel=1))
+    o2, _ = run_case(m, c, False, tuning=dict(kernel=2))
+    check(o1, ref, "bf16"), check(o2, ref, "bf16")
+
+
+def test_two_phase_calls_equal_one_call(m):
+    c = mi.random_case(39, 2, 32, 2048, 128, 128, cache="bf16", lens="ragged")
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.from_numpy(c["lens"]).to(DEV)
+    tn = dict(splits=4)
+    o1 = m.mqa_decode_step(q, K, V, lens, tuning=tn)
+    ws = torch.empty(m.mqa_decode_workspace_bytes(2, 32, 2048, 128), dtype=torch.uint8, device=DEV)
+    o2 = torch.full_like(o1, float("nan"))
+    m.mqa_decode_partials(q, K, V, lens, o2, ws, tuning=tn)
+    m.mqa_decode_combine(lens, o2, 2048, 128, m.MQA_BF16, ws, tuning=tn)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+
+
+# ----------------------------------------------------------------- append
+@pytest.mark.parametrize("cache,mh", [("bf16", False), ("bf16", True), ("f32", False), ("f32", True)])
+def test_append_bit_exact(m, cache, mh):
+    g = mi.rng(2000, 1 + int(mh))
+    b, h, cap, k, v = 5, 3, 6, 16, 24
+    hk = h if mh else 1
+    shape_k = (b, h, cap, k) if mh else (b, cap, k)
+    shape_v = (b, h, cap, v) if mh else (b, cap, v)
+    lens0 = np.array([0, 3, 6, 5, 1], dtype=np.int32)           # sequence 2 is full
+    k_new = g.standard_normal((b, hk, k), dtype=np.float32) * np.float32(3)
+    v_new = g.standard_normal((b, hk, v), dtype=np.float32)
+    k_new[0, 0, :4] = [1.00390625, 1.01171875, -0.0, 3e-41]      # ties to even, signed zero, subnormal
+    tdt = torch.bfloat16 if cache == "bf16" else torch.float32
+    K = torch.zeros(shape_k, dtype=tdt, device=DEV)
+    V = torch.zeros(shape_v, dtype=tdt, device=DEV)
+    lens = torch.from_numpy(lens0.copy()).to(DEV)
+    kn = torch.from_numpy(k_new if mh else k_new[:, 0]).contiguous().to(DEV)
+    vn = torch.from_numpy(v_new if mh else v_new[:, 0]).contiguous().to(DEV)
+    m.mqa_append_kv(K, V, kn, vn, lens)
+    torch.cuda.synchronize()
+    Kr, Vr = np.zeros(shape_k), np.zeros(shape_v)
+    lr = lens0.astype(np.int64)
+    orc.append_kv(Kr, Vr, k_new if mh else k_new[:, 0], v_new if mh else v_new[:, 0], lr, cache)
+    assert np.array_equal(lens.cpu().numpy(), lr)
+    assert np.array_equal(K.double().cpu().numpy(), Kr)
+    assert np.array_equal(V.double().cpu().numpy(), Vr)
+    assert np.array_equal(np.signbit(K.double().cpu().numpy()), np.signbit(Kr))
+
+
+# ----------------------------------------------------------------- projections
+@pytest.mark.parametrize("rows,d,h,kv", [(1, 1024, 8, 128), (128, 1024, 8, 128), (37, 72, 3, 40), (5, 8, 1, 8)])
+def test_projections(m, rows, d, h, kv):
+    g = mi.rng(3000, rows + d)
+    x = g.standard_normal((rows, d), dtype=np.float32)
+    P_q = g.standard_normal((h, d, kv), dtype=np.float32) / np.float32(np.sqrt(d))
+    P_k = g.standard_normal((d, kv), dtype=np.float32) / np.float32(np.sqrt(d))
+    o = g.standard_normal((rows, h, kv), dtype=np.float32)
+    P_o = g.standard_normal((h, d, kv), dtype=np.float32) / np.float32(np.sqrt(h * kv))
+    dx, dPq, dPk, do, dPo = (torch.from_numpy(a).to(DEV) for a in (x, P_q, P_k, o, P_o))
+    got = m.mqa_project_qkvo(m.MQA_PROJ_Q, dx, dPq)
+    assert np.max(np.abs(got.cpu().numpy() - orc.project_q(x, P_q))) <= 1e-5
+    got = m.mqa_project_qkvo(m.MQA_PROJ_KV_MH, dx, dPq)
+    assert np.max(np.abs(got.cpu().numpy() - orc.project_kv_mh(x, P_q))) <= 1e-5
+    got = m.mqa_project_qkvo(m.MQA_PROJ_KV, dx, dPk)
+    assert np.max(np.abs(got.cpu().numpy() - orc.project_kv(x, P_k))) <= 1e-5
+    got = m.mqa_project_qkvo(m.MQA_PROJ_O, do, dPo)
+    assert np.max(np.abs(got.cpu().numpy() - orc.project_o(o, P_o))) <= 1e-5
+
+
+# ----------------------------------------------------------------- workload 1: one float32 step against a memory
+def test_config1_single_step_fp32(m):
+    c = mi.config1()
+    h, d, k = c["P_q"].shape
+    mem = c["M"].shape[1]
+    x = torch.from_numpy(c["x"]).to(DEV)
+    M = torch.from_numpy(c["M"][0]).to(DEV)
+    lens = torch.full((1,), mem, dtype=torch.int32, device=DEV)
+    # multi-query
+    q = m.mqa_project_qkvo(m.MQA_PROJ_Q, x, torch.from_numpy(c["P_q"]).to(DEV))
+    K = m.mqa_project_qkvo(m.MQA_PROJ_KV, M, torch.from_numpy(c["P_k"]).to(DEV))[None]
+    V = m.mqa_project_qkvo(m.MQA_PROJ_KV, M, torch.from_numpy(c["P_v"]).to(DEV))[None]
+    o = m.mqa_decode_step(q, K.contiguous(), V.contiguous(), lens)
+    y = m.mqa_project_qkvo(m.MQA_PROJ_O, o, torch.from_numpy(c["P_o"]).to(DEV))
+    ref = orc.multiquery_attention(c["x"][0], c["M"][0], c["P_q"], c["P_k"], c["P_v"], c["P_o"])
+    err = check(y[0], ref, "f32", "config 1 multi-query y")
+    print(f"config 1 multi-query: max abs err {err:.2e}, max |y| {np.abs(ref).max():.2e}")
+    # multi-head twin
+    Kh = m.mqa_project_qkvo(m.MQA_PROJ_KV_MH, M, torch.from_numpy(c["P_k_mh"]).to(DEV))     # [m,h,k]
+    Vh = m.mqa_project_qkvo(m.MQA_PROJ_KV_MH, M, torch.from_numpy(c["P_v_mh"]).to(DEV))
+    Kh = Kh.permute(1, 0, 2).contiguous()[None]
+    Vh = Vh.permute(1, 0, 2).contiguous()[None]
+    o = m.mha_decode_step(q, Kh, Vh, lens)
+    y = m.mqa_project_qkvo(m.MQA_PROJ_O, o, torch.from_numpy(c["P_o"]).to(DEV))
+    ref = orc.multihead_attention(c["x"][0], c["M"][0], c["P_q"], c["P_k_mh"], c["P_v_mh"], c["P_o"])
+    check(y[0], ref, "f32", "config 1 multi-head y")
+
+
+# ----------------------------------------------------------------- workload 2: incremental decoding, every step
+@pytest.mark.parametrize("multi_head", [False, True])
+def test_config2_incremental(m, multi_head):
+    b, steps = 128, 128
+    c = mi.config2(b=b, steps=steps)
+    h, d, k = c["P_q"].shape
+    v = c["P_o"].shape[2]
+    Pk_np, Pv_np = (c["P_k_mh"], c["P_v_mh"]) if multi_head else (c["P_k"], c["P_v"])
+    P_q, P_k, P_v, P_o = (torch.from_numpy(a).to(DEV) for a in (c["P_q"], Pk_np, Pv_np, c["P_o"]))
+    kshape = (b, h, steps, k) if multi_head else (b, steps, k)
+    vshape = (b, h, steps, v) if multi_head else (b, steps, v)
+    nan = float("nan")
+    K = torch.full(kshape, nan, dtype=torch.bfloat16, device=DEV)
+    V = torch.full(vshape, nan, dtype=torch.bfloat16, device=DEV)
+    lens = torch.zeros(b, dtype=torch.int32, device=DEV)
+    Kr, Vr = np.full(kshape, np.nan), np.full(vshape, np.nan)
+    lr = np.zeros(b, dtype=np.int64)
+    X = torch.from_numpy(c["X"]).to(DEV)
+    kv_mode = m.MQA_PROJ_KV_MH if multi_head else m.MQA_PROJ_KV
+    step_fn = orc.mha_incremental_step if multi_head else orc.mqa_incremental_step
+    dec = m.mha_decode_step if multi_head else m.mqa_decode_step
+    ys, worst_o, worst_y = [], 0.0, 0.0
+    for t in range(steps):
+        x = X[:, t].contiguous()
+        q = m.mqa_project_qkvo(m.MQA_PROJ_Q, x, P_q)
+        kn = m.mqa_project_qkvo(kv_mode, x, P_k)
+        vn = m.mqa_project_qkvo(kv_mode, x, P_v)
+        m.mqa_append_kv(K, V, kn, vn, lens)
+        o = dec(q, K, V, lens)
+        y = m.mqa_project_qkvo(m.MQA_PROJ_O, o, P_o)
+        y_ref, o_ref, _ = step_fn(c["X"][:, t], Kr, Vr, lr, c["P_q"], Pk_np, Pv_np, c["P_o"], cache="bf16")
+        worst_o = max(worst_o, check(o, o_ref, "bf16", f"step {t} o"))
+        worst_y = max(worst_y, check(y, y_ref, "bf16", f"step {t} y"))
+        ys.append(y.cpu().numpy())
+    assert np.array_equal(lens.cpu().numpy(), np.full(b, steps))
+    # the caches agree except where a projection landed within float32 rounding of a bf16 tie
+    Kg = K.double().cpu().numpy()
+    assert np.mean(Kg != Kr) < 1e-3 and np.max(np.abs(Kg - Kr)) <= 2.0 ** -5
+    # stacked incremental outputs == one causally masked parallel call (first 8 sequences)
+    nb = 8
+    mask = orc.causal_mask(nb, h, steps)
+    fn = orc.multihead_attention_batched if multi_head else orc.multiquery_attention_batched
+    Y = fn(c["X"][:nb], c["X"][:nb], mask, c["P_q"], Pk_np, Pv_np, c["P_o"], kv_round=orc.round_to_bf16)
+    got = np.stack(ys, axis=1)[:nb].astype(np.float64)
+    err = np.max(np.abs(got - Y))
+    assert err <= 2e-2 and err <= 1e-2 * np.max(np.abs(Y))
+    print(f"config 2 {'mha' if multi_head else 'mqa'}: worst o err {worst_o:.2e}, worst y err {worst_y:.2e}, vs parallel {err:.2e}")
