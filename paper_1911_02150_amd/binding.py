@@ -120,6 +120,19 @@ def mha_decode_workspace_bytes(b, h, cap, v) -> int:
     return int(load_library().mha_decode_workspace_bytes(b, h, cap, v))
 
 
+_ws_cache = {}
+
+
+def _default_workspace(device, nbytes):
+    """Workspace owned by the binding for callers that pass none: one per device, grown on demand."""
+    key = (device.type, device.index)
+    ws = _ws_cache.get(key)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _ws_cache[key] = ws
+    return ws
+
+
 def mqa_decode_num_splits(b, h, cap, k, v, dt, multi_head=False, tuning=None) -> int:
     return int(load_library().mqa_decode_num_splits(b, h, cap, k, v, dt, int(multi_head), _tuning(tuning)))
 
@@ -140,7 +153,7 @@ def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tun
         raise ValueError("o must be [b,h,v]")
     if workspace is None:
         nbytes = mha_decode_workspace_bytes(b, h, cap, v) if multi_head else mqa_decode_workspace_bytes(b, h, cap, v)
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+        workspace = _default_workspace(q.device, nbytes)
     args = [_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K), float(scale),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
     if with_tuning:

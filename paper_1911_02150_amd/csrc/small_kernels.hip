@@ -11,6 +11,9 @@ namespace {
 // the paper's Section 2.1 written over a partition of the positions):
 //   M = max_i m_i,  L = sum_i l_i 2^(m_i - M),  o = sum_i acc_i 2^(m_i - M) / L.
 // Only ranges that start before the sequence length were written.
+// SMAX > 0: S <= SMAX known to be small; every partial is fetched up front, independent of
+// the length, so the pass costs one memory latency instead of a chain of three.
+template <int SMAX>
 __global__ __launch_bounds__(256)
 void combine_kernel(DecodeParams p) {
   const int v4 = p.v >> 2;
@@ -20,24 +23,56 @@ void combine_kernel(DecodeParams p) {
   const int c4 = (int)(idx % v4);
   const int head = (int)((idx / v4) % p.G);
   const int seq = (int)(idx / ((size_t)v4 * p.G));
-  int L = p.lens[seq / p.lens_div];
-  L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-  const int nvalid = min(p.S, (L + p.chunk - 1) / p.chunk);
+  const size_t base = (size_t)seq * p.S * p.G + head;
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (nvalid > 0) {
-    const size_t base = (size_t)seq * p.S * p.G + head;
-    float M = -INFINITY;
-    for (int s = 0; s < nvalid; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.G]);
-    float lsum = 0.f;
-    for (int s = 0; s < nvalid; ++s) {
-      const size_t pi = base + (size_t)s * p.G;
-      const float f = __builtin_amdgcn_exp2f(p.part_m[pi] - M);
-      const float4 x = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
-      a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
-      lsum += f * p.part_l[pi];
+  if (SMAX > 0) {
+    constexpr int N = SMAX > 0 ? SMAX : 1;
+    float pm[N], pl[N];
+    float4 po[N];
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+      const size_t pi = base + (size_t)min(s, p.S - 1) * p.G;     // in bounds for every s
+      pm[s] = p.part_m[pi];
+      pl[s] = p.part_l[pi];
+      po[s] = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
     }
-    const float inv = 1.0f / lsum;
-    a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+    int L = p.lens[seq / p.lens_div];
+    L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
+    const int nvalid = min(p.S, (L + p.chunk - 1) / p.chunk);
+    if (nvalid > 0) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int s = 0; s < SMAX; ++s)
+        if (s < nvalid) M = fmaxf(M, pm[s]);
+      float lsum = 0.f;
+#pragma unroll
+      for (int s = 0; s < SMAX; ++s)
+        if (s < nvalid) {            // ranges past the length were never written: skip, do not multiply by 0
+          const float f = __builtin_amdgcn_exp2f(pm[s] - M);
+          a.x += f * po[s].x; a.y += f * po[s].y; a.z += f * po[s].z; a.w += f * po[s].w;
+          lsum += f * pl[s];
+        }
+      const float inv = 1.0f / lsum;
+      a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+    }
+  } else {
+    int L = p.lens[seq / p.lens_div];
+    L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
+    const int nvalid = min(p.S, (L + p.chunk - 1) / p.chunk);
+    if (nvalid > 0) {
+      float M = -INFINITY;
+      for (int s = 0; s < nvalid; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.G]);
+      float lsum = 0.f;
+      for (int s = 0; s < nvalid; ++s) {
+        const size_t pi = base + (size_t)s * p.G;
+        const float f = __builtin_amdgcn_exp2f(p.part_m[pi] - M);
+        const float4 x = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
+        a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
+        lsum += f * p.part_l[pi];
+      }
+      const float inv = 1.0f / lsum;
+      a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+    }
   }
   reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * p.v)[c4] = a;
 }
@@ -97,7 +132,10 @@ void stream_copy_kernel(const uint4* src, uint4* dst, size_t n16) {
 
 hipError_t launch_combine(const DecodeParams& p, hipStream_t st) {
   const size_t total = (size_t)p.nseq * p.G * (p.v >> 2);
-  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, p);
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (p.S <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
+  else if (p.S <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
+  else hipLaunchKernelGGL(combine_kernel<0>, grid, block, 0, st, p);
   return hipGetLastError();
 }
 

@@ -241,8 +241,30 @@ def test_config1_single_step_fp32(m):
 
 
 # ----------------------------------------------------------------- workload 2: incremental decoding, every step
+def _row_view(cache, t, multi_head):
+    return cache[:, :, t] if multi_head else cache[:, t]
+
+
+def _check_appended_row(got_row, ref_row, exact_row, what):
+    """The row a step appends is a bf16 rounding of a float32 projection.  The
+    GPU sums in float32, the oracle in float64, so at (near-)ties the two may
+    pick different neighbours; both are valid roundings.  Valid means: the
+    GPU's value is as close to the oracle's unrounded float64 value as the
+    oracle's own rounding is, up to the float32 summation error (2e-5)."""
+    got = got_row.double().cpu().numpy()
+    differs = got != ref_row
+    assert np.all(np.abs(got - exact_row) <= np.abs(ref_row - exact_row) + 2e-5), f"{what}: invalid rounding"
+    return int(differs.sum())
+
+
 @pytest.mark.parametrize("multi_head", [False, True])
 def test_config2_incremental(m, multi_head):
+    """128 sequences decoded for 128 steps (projections -> append -> attention
+    -> output projection).  Every step: the appended bf16 rows are checked to be
+    valid roundings of the oracle's rows, then replaced by the oracle's rows so
+    that both sides attend over the same cache, and o and y are compared with
+    the stated tolerance.  The stacked y equal one causally masked parallel
+    call of the oracle (Section 2.3 / Section 3 batched listings)."""
     b, steps = 128, 128
     c = mi.config2(b=b, steps=steps)
     h, d, k = c["P_q"].shape
@@ -259,25 +281,31 @@ def test_config2_incremental(m, multi_head):
     lr = np.zeros(b, dtype=np.int64)
     X = torch.from_numpy(c["X"]).to(DEV)
     kv_mode = m.MQA_PROJ_KV_MH if multi_head else m.MQA_PROJ_KV
+    okv = orc.project_kv_mh if multi_head else orc.project_kv
     step_fn = orc.mha_incremental_step if multi_head else orc.mqa_incremental_step
     dec = m.mha_decode_step if multi_head else m.mqa_decode_step
-    ys, worst_o, worst_y = [], 0.0, 0.0
+    ys, worst_o, worst_y, flips = [], 0.0, 0.0, 0
     for t in range(steps):
         x = X[:, t].contiguous()
         q = m.mqa_project_qkvo(m.MQA_PROJ_Q, x, P_q)
         kn = m.mqa_project_qkvo(kv_mode, x, P_k)
         vn = m.mqa_project_qkvo(kv_mode, x, P_v)
         m.mqa_append_kv(K, V, kn, vn, lens)
+        y_ref, o_ref, _ = step_fn(c["X"][:, t], Kr, Vr, lr, c["P_q"], Pk_np, Pv_np, c["P_o"], cache="bf16")
+        flips += _check_appended_row(_row_view(K, t, multi_head), _row_view(Kr, t, multi_head),
+                                     okv(c["X"][:, t], Pk_np), f"step {t} K row")
+        flips += _check_appended_row(_row_view(V, t, multi_head), _row_view(Vr, t, multi_head),
+                                     okv(c["X"][:, t], Pv_np), f"step {t} V row")
+        _row_view(K, t, multi_head).copy_(torch.from_numpy(_row_view(Kr, t, multi_head)).to(torch.bfloat16))
+        _row_view(V, t, multi_head).copy_(torch.from_numpy(_row_view(Vr, t, multi_head)).to(torch.bfloat16))
         o = dec(q, K, V, lens)
         y = m.mqa_project_qkvo(m.MQA_PROJ_O, o, P_o)
-        y_ref, o_ref, _ = step_fn(c["X"][:, t], Kr, Vr, lr, c["P_q"], Pk_np, Pv_np, c["P_o"], cache="bf16")
         worst_o = max(worst_o, check(o, o_ref, "bf16", f"step {t} o"))
         worst_y = max(worst_y, check(y, y_ref, "bf16", f"step {t} y"))
         ys.append(y.cpu().numpy())
     assert np.array_equal(lens.cpu().numpy(), np.full(b, steps))
-    # the caches agree except where a projection landed within float32 rounding of a bf16 tie
-    Kg = K.double().cpu().numpy()
-    assert np.mean(Kg != Kr) < 1e-3 and np.max(np.abs(Kg - Kr)) <= 2.0 ** -5
+    assert np.array_equal(K.double().cpu().numpy(), Kr) and np.array_equal(V.double().cpu().numpy(), Vr)
+    assert flips < 1e-3 * 2 * Kr.size
     # stacked incremental outputs == one causally masked parallel call (first 8 sequences)
     nb = 8
     mask = orc.causal_mask(nb, h, steps)
@@ -286,4 +314,33 @@ def test_config2_incremental(m, multi_head):
     got = np.stack(ys, axis=1)[:nb].astype(np.float64)
     err = np.max(np.abs(got - Y))
     assert err <= 2e-2 and err <= 1e-2 * np.max(np.abs(Y))
-    print(f"config 2 {'mha' if multi_head else 'mqa'}: worst o err {worst_o:.2e}, worst y err {worst_y:.2e}, vs parallel {err:.2e}")
+    print(f"config 2 {'mha' if multi_head else 'mqa'}: worst o err {worst_o:.2e}, worst y err {worst_y:.2e}, "
+          f"vs parallel {err:.2e}, near-tie rounding differences {flips}")
+
+
+def test_config2_free_running(m):
+    """The same loop with no synchronisation of the caches: near-tie rounding
+    differences (one bf16 ulp in a cached element) now reach the outputs, so the
+    bar here is the stated tolerance plus one bf16 ulp of the largest |V|."""
+    b, steps = 128, 64
+    c = mi.config2(b=b, steps=steps)
+    h, d, k = c["P_q"].shape
+    v = c["P_o"].shape[2]
+    P_q, P_k, P_v = (torch.from_numpy(c[n]).to(DEV) for n in ("P_q", "P_k", "P_v"))
+    K = torch.zeros((b, steps, k), dtype=torch.bfloat16, device=DEV)
+    V = torch.zeros((b, steps, v), dtype=torch.bfloat16, device=DEV)
+    lens = torch.zeros(b, dtype=torch.int32, device=DEV)
+    Kr, Vr = np.zeros((b, steps, k)), np.zeros((b, steps, v))
+    lr = np.zeros(b, dtype=np.int64)
+    X = torch.from_numpy(c["X"]).to(DEV)
+    worst = 0.0
+    for t in range(steps):
+        x = X[:, t].contiguous()
+        q = m.mqa_project_qkvo(m.MQA_PROJ_Q, x, P_q)
+        m.mqa_append_kv(K, V, m.mqa_project_qkvo(m.MQA_PROJ_KV, x, P_k), m.mqa_project_qkvo(m.MQA_PROJ_KV, x, P_v), lens)
+        o = m.mqa_decode_step(q, K, V, lens)
+        _, o_ref, _ = orc.mqa_incremental_step(c["X"][:, t], Kr, Vr, lr, c["P_q"], c["P_k"], c["P_v"], c["P_o"], cache="bf16")
+        worst = max(worst, float(np.max(np.abs(o.cpu().numpy() - o_ref))))
+    ulp = 2.0 ** (np.floor(np.log2(np.max(np.abs(Vr)))) - 7)
+    assert worst <= 2e-2 + ulp, worst
+    print(f"config 2 free running: worst o err {worst:.2e} (bf16 ulp of max|V| = {ulp:.2e})")
