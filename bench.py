@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-query-attention decode step on one MI355X.
+
+Workload ("long_context_probe", the configuration the headline metric is quoted
+on): one MQA decode step with b=64 sequences, m=8192 cached positions, h=32
+query heads, k=v=128, bf16 K/V cache ~N(0,1), q fp32 ~N(0,1)/sqrt(k), all
+sequences full length.  One step = one mqa_decode_step call (logits, softmax,
+weighted sum over the whole cache, including the merge of the position ranges).
+Inputs are seeded synthetic tensors resident in HBM before the timed region.
+Several distinct K/V sets (>= 1 GiB in total, four times the 256 MB Infinity
+Cache) are rotated so that every step streams its cache from HBM.
+
+Prints ONE JSON line: the whole-step K/V throughput (`value`, GB/s on the K/V
+bytes a step must read), the step latency, a roofline object for the dominant
+kernel timed alone, the multi-head twin (32x the bytes) and the float64 CPU
+oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--skip-mha", action="store_true", help="do not time the 8 GiB multi-head twin")
+    ap.add_argument("--skip-cpu-baseline", action="store_true", help="do not time the CPU oracle")
+    ap.add_argument("--splits", type=int, default=0, help="override the number of position ranges")
+    ap.add_argument("--flags", type=int, default=0, help="override kernel variant flags")
+    return ap.parse_args()
+
+
+def time_region(fn, steps, warmup, settle_s=0.25):
+    """W untimed warm-up calls, then exactly `steps` timed calls between two events on the
+    current stream.  Before the warm-up the same call is repeated for `settle_s` seconds so
+    that clocks and power state have settled (a cold first region reads several us slow)."""
+    import torch
+    t_end = time.perf_counter() + settle_s
+    while time.perf_counter() < t_end:
+        for i in range(20):
+            fn(i)
+        torch.cuda.synchronize()
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps          # ms per call
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel, from the committed counter summary (or None)."""
+    path = os.path.join(ROOT, "profiles", "mqa_decode_mfma_long_context_probe_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(q, K_bits, V_bits, budget_s=12.0):
+    """The float64 oracle on the host cores over whole passes of the same workload."""
+    import numpy as np
+    import mqa_inputs as mi
+    from oracle import mqa_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    b, m, k = K_bits.shape
+    lens = np.full((b,), m, dtype=np.int64)
+    done, t0 = 0, time.perf_counter()
+    while True:
+        i = done % b
+        orc.mqa_decode(q[i:i + 1], mi.bf16_bits_to_f64(K_bits[i:i + 1]), mi.bf16_bits_to_f64(V_bits[i:i + 1]), lens[i:i + 1])
+        done += 1
+        el = time.perf_counter() - t0
+        if (el >= budget_s and done >= 8) or done >= 200 * b:
+            break
+    bytes_done = done * m * 2 * k * 2
+    return {
+        "value": bytes_done / el / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{done} of the {b} sequences (m={m}, h={q.shape[1]}) through oracle.mqa_decode in float64, "
+                  f"{el:.1f} s; bytes counted as the bf16 K/V bytes of those sequences",
+        "step_seconds_extrapolated": el / done * b,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import mqa_inputs as mi
+    import paper_1911_02150_amd as m
+
+    m.load_library()                      # raises if the HIP library has not been built
+    dev = torch.device("cuda:0")
+    cfg = mi.CONFIGS[4]
+    b, h, cap, k, v = cfg["b"], cfg["h"], cfg["cap"], cfg["k"], cfg["v"]
+    kv_bytes = b * cap * (k + v) * 2
+    nbuf = 5                              # 5 x 256 MiB of distinct K/V
+
+    # ---- seeded inputs, resident in HBM before timing
+    q_np = mi.config4_q(b, h, k)
+    K_np, V_np = mi.config4_kv(b=b * nbuf, m=cap, k=k, v=v, threads=min(16, os.cpu_count() or 8))
+    q = torch.from_numpy(q_np).to(dev)
+    Ks = [mi.bits_to_torch_bf16(K_np[i * b:(i + 1) * b]).to(dev) for i in range(nbuf)]
+    Vs = [mi.bits_to_torch_bf16(V_np[i * b:(i + 1) * b]).to(dev) for i in range(nbuf)]
+    lens = torch.full((b,), cap, dtype=torch.int32, device=dev)
+    o = torch.empty((b, h, v), dtype=torch.float32, device=dev)
+    ws = torch.empty(m.mqa_decode_workspace_bytes(b, h, cap, v), dtype=torch.uint8, device=dev)
+    tuning = dict(splits=args.splits, flags=args.flags) if (args.splits or args.flags) else None
+    splits = m.mqa_decode_num_splits(b, h, cap, k, v, m.MQA_BF16, False, tuning)
+
+    # ---- the timed region: K whole steps
+    def step(i):
+        m.mqa_decode_step(q, Ks[i % nbuf], Vs[i % nbuf], lens, o=o, workspace=ws, tuning=tuning)
+
+    ms_step = time_region(step, args.steps, args.warmup)
+    step_us = ms_step * 1e3
+    value = kv_bytes / (ms_step * 1e-3) / 1e9
+
+    # ---- dominant kernel alone (the streaming pass), same launch configuration
+    def main_only(i):
+        m.mqa_decode_partials(q, Ks[i % nbuf], Vs[i % nbuf], lens, o, ws, tuning=tuning)
+
+    ms_main = time_region(main_only, args.steps, args.warmup)
+    alg_bytes = kv_bytes + b * h * k * 4 + b * h * v * 4 + b * 4
+    achieved = alg_bytes / (ms_main * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic_from_profile(),
+        "kernel": "decode_mfma_kernel", "avg_launch_us": ms_main * 1e3, "algorithmic_bytes": alg_bytes,
+    }
+
+    # ---- the box's achievable streaming-read rate, same run
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    sink = torch.zeros(4096, dtype=torch.float32, device=dev)
+    ms_read = time_region(lambda i: m.mqa_stream_read(big, sink), 20, 3)
+    stream_read_gbps = big.numel() / (ms_read * 1e-3) / 1e9
+    big2 = torch.empty_like(big)          # plain copy of known size: the reference for the byte counters
+    ms_copy = time_region(lambda i: m.mqa_stream_copy(big, big2), 10, 2)
+    stream_copy_gbps = 2 * big.numel() / (ms_copy * 1e-3) / 1e9
+    del big, big2
+
+    # ---- multi-head twin: per-head K/V, 32x the bytes
+    mha = None
+    if not args.skip_mha:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(mi.SEED_BASE + 4)
+        Kh = torch.empty((b, h, cap, k), dtype=torch.bfloat16, device=dev)
+        Vh = torch.empty((b, h, cap, v), dtype=torch.bfloat16, device=dev)
+        for i in range(b):
+            Kh[i].copy_(torch.randn((h, cap, k), device=dev, generator=gen))
+            Vh[i].copy_(torch.randn((h, cap, v), device=dev, generator=gen))
+        wsh = torch.empty(m.mha_decode_workspace_bytes(b, h, cap, v), dtype=torch.uint8, device=dev)
+        ms_mha = time_region(lambda i: m.mha_decode_step(q, Kh, Vh, lens, o=o, workspace=wsh), 10, 2)
+        mha_bytes = kv_bytes * h
+        mha = {"step_us": ms_mha * 1e3, "kv_bytes": mha_bytes, "kv_GBps": mha_bytes / (ms_mha * 1e-3) / 1e9,
+               "frac_of_peak": mha_bytes / (ms_mha * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               "mha_over_mqa_time": ms_mha / ms_step, "kv_bytes_ratio": h,
+               "data": "torch.randn on the device, seeded (timing only; parity uses the host-seeded blocks)"}
+        del Kh, Vh
+
+    cpu = None
+    if not args.skip_cpu_baseline:
+        cpu = cpu_baseline(q_np, K_np[:b], V_np[:b])
+
+    out = {
+        "metric": "MQA decode-step µs + achieved HBM GB/s on K/V bytes (fraction of peak) vs MHA",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "long_context_probe: MQA decode step b=64 m=8192 h=32 k=v=128, bf16 K/V, all lengths full",
+                   "b": b, "h": h, "m": cap, "k": k, "v": v, "kv_bytes_per_step": kv_bytes,
+                   "kv_sets_rotated": nbuf, "position_ranges": splits},
+        "step_us": step_us, "tokens_per_s": b / (ms_step * 1e-3), "frac_of_peak": value / HBM_PEAK_GBPS,
+        "stream_read_GBps": stream_read_gbps, "stream_copy_GBps": stream_copy_gbps,
+        "roofline": roofline, "mha": mha, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,7 +10,11 @@ namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-constexpr int kTargetBlocks = 1024;   // workgroups wanted in flight (256 CUs x 2 x 2)
+constexpr int kTargetBlocks = 256;    // one workgroup per compute unit: measured best for the streaming pass
+
+#ifdef MQA_TIMELINE
+long long* g_timeline = nullptr;
+#endif
 
 struct Plan {
   bool use_mfma;
@@ -93,6 +97,9 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
   p.k = k; p.v = v; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
+#ifdef MQA_TIMELINE
+  p.timeline = g_timeline;
+#endif
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (phase & 1) {
     hipError_t e = pl.use_mfma ? launch_decode_mfma(p, tn.flags, st)
@@ -215,6 +222,10 @@ int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (misaligned(src) || misaligned(dst)) return MQA_ERR_ALIGN;
   return launch_stream_copy(src, dst, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
 }
+
+#ifdef MQA_TIMELINE
+void mqa_debug_timeline(long long* p) { g_timeline = p; }
+#endif
 
 const char* mqa_status_string(int status) {
   switch (status) {

@@ -28,6 +28,9 @@ struct DecodeParams {
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
   float qscale;          // scale * log2(e): logits are kept in the log2 domain
+#ifdef MQA_TIMELINE
+  long long* timeline;   // debug builds only: [waves][8] wall-clock stamps
+#endif
 };
 
 struct Tuning {

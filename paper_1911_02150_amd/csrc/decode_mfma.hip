@@ -76,6 +76,12 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
   }
 }
 
+#ifdef MQA_TIMELINE   // debug builds: per-wave wall-clock stamps (100 MHz counter shared by all CUs)
+#define MQA_STAMP(i) do { if (p.timeline && lane == 0) p.timeline[((size_t)blockIdx.x * NW + wave) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define MQA_STAMP(i) do { } while (0)
+#endif
+
 template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL>
 __global__ __launch_bounds__(NW * 64, (HB <= 2 ? 2 : 1))
 void decode_mfma_kernel(DecodeParams p) {
@@ -99,34 +105,54 @@ void decode_mfma_kernel(DecodeParams p) {
   const int krow_in_tile = 4 * (i16 & 3) + (i16 >> 2);
   const int rmax = p.cap - 1;
 
-  u32x4 kr[2][4], vr[8];
-  auto load_k = [&](int t) {
+  // A tile past the end of the range is "fetched" from one fixed in-bounds address by all
+  // lanes (a single cached line), so the prefetch needs no branch and costs no bandwidth.
+  // (Keeping a second tile per wave in flight was measured slower: the memory pipeline
+  // accepts the extra requests no sooner.)
+  struct Tile { u32x4 kr[2][4]; u32x4 vr[8]; };
+  Tile tb;
+  auto load_k = [&](Tile& tl, int t, bool real) {
     const int p0 = begin + 32 * t;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const int row = min(p0 + 16 * u + krow_in_tile, rmax);
-      const u32x4* src = Kbase + (size_t)row * kRowU4 + g;
+      const int row = real ? min(p0 + 16 * u + krow_in_tile, rmax) : begin;
+      const u32x4* src = Kbase + (size_t)row * kRowU4 + (real ? g : 0);
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) kr[u][s4] = ld16<NTL>(src + 4 * s4);
+      for (int s4 = 0; s4 < 4; ++s4) tl.kr[u][s4] = ld16<NTL>(src + (real ? 4 * s4 : 0));
     }
   };
-  auto load_v = [&](int t) {
+  auto load_v = [&](Tile& tl, int t, bool real) {
     const int p0 = begin + 32 * t;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int row = min(p0 + 4 * e + g, rmax);
-      vr[e] = ld16<NTL>(Vbase + (size_t)row * kRowU4 + i16);
+      const int row = real ? min(p0 + 4 * e + g, rmax) : begin;
+      tl.vr[e] = ld16<NTL>(Vbase + (size_t)row * kRowU4 + (real ? i16 : 0));
     }
   };
 
-  // The wave's first tile is requested before the length is known and before q
-  // is staged, so the start-up latencies overlap.  (Rows are in bounds for any length.)
-  int t = wave;
-  if (begin + 32 * t <= rmax) {
-    load_k(t);
-    load_v(t);
+  MQA_STAMP(0);
+  // q is requested first (loads return in order, and q is needed first), then the wave's
+  // first K/V tile -- both before the length is known, so the start-up latencies overlap.
+  // (Rows are in bounds for any length.)
+  constexpr int QITEMS = (NH * 16 + NT - 1) / NT;        // (head, 16-byte chunk) items per thread
+  float4 qa[QITEMS], qb[QITEMS];
+#pragma unroll
+  for (int it = 0; it < QITEMS; ++it) {
+    const int idx = tid + it * NT;
+    const int hl = idx >> 4, c = idx & 15;               // head in block, 8-float chunk of the row
+    qa[it] = qb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (idx < NH * 16 && head0 + hl < p.G) {
+      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * p.G + head0 + hl) * kD + c * 8);
+      qa[it] = src[0];
+      qb[it] = src[1];
+    }
   }
-
+  {
+    const bool real = begin + 32 * wave <= rmax;
+    load_k(tb, wave, real);
+    load_v(tb, wave, real);
+  }
+  MQA_STAMP(1);
   int L = p.lens[seq / p.lens_div];
   L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
   const int end = min(begin + p.chunk, L);
@@ -146,20 +172,15 @@ void decode_mfma_kernel(DecodeParams p) {
   // ---- q -> LDS as MFMA B operands: qs[(hb*4 + s)*64 + lane] (hi), then lo
   u32x4* qs = reinterpret_cast<u32x4*>(smem_raw);
   constexpr int QOPS = HB * 4 * 64;
-  for (int idx = tid; idx < NH * 16; idx += NT) {
-    const int hl = idx >> 4, c = idx & 15;          // head in block, 16-byte chunk of the row
+#pragma unroll
+  for (int it = 0; it < QITEMS; ++it) {
+    const int idx = tid + it * NT;
+    if (idx >= NH * 16) break;
+    const int hl = idx >> 4, c = idx & 15;
     const int s4 = c >> 2, gg = c & 3;              // chunk c = 4s + g
-    float x[8];
-    if (head0 + hl < p.G) {
-      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * p.G + head0 + hl) * kD + c * 8);
-      float4 a = src[0], b = src[1];
-      x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    float x[8] = {qa[it].x, qa[it].y, qa[it].z, qa[it].w, qb[it].x, qb[it].y, qb[it].z, qb[it].w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] *= p.qscale;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = 0.f;
-    }
+    for (int e = 0; e < 8; ++e) x[e] *= p.qscale;
     u32x4 hi, lo;
     split8(x, hi, lo);
     const int slot = (((hl >> 4) * 4 + s4) * 64) + (hl & 15) + 16 * gg;
@@ -167,6 +188,7 @@ void decode_mfma_kernel(DecodeParams p) {
     qs[QOPS + slot] = lo;
   }
   __syncthreads();
+  MQA_STAMP(2);
 
   floatx4 acc[HB][8];
   float m_run[HB], l_run[HB];
@@ -178,10 +200,11 @@ void decode_mfma_kernel(DecodeParams p) {
     for (int j = 0; j < 8; ++j) acc[hb][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (; t < ntiles; t += NW) {
+  // one tile: logits, online softmax, weighted sum; refills the tile's registers with tile tn
+  auto process = [&](Tile& tl, int t, int tn) {
     const int p0 = begin + 32 * t;
-    const int tn = min(t + NW, ntiles - 1);
     const bool tail = p0 + 32 > end;
+    const bool more = tn < ntiles;
 
     // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
     floatx4 sc[2][HB];
@@ -192,16 +215,17 @@ void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
       for (int s4 = 0; s4 < 4; ++s4) {
         const u32x4 qh = qs[(hb * 4 + s4) * 64 + lane];
-        sc[0][hb] = mfma16(kr[0][s4], qh, sc[0][hb]);
-        sc[1][hb] = mfma16(kr[1][s4], qh, sc[1][hb]);
+        sc[0][hb] = mfma16(tl.kr[0][s4], qh, sc[0][hb]);
+        sc[1][hb] = mfma16(tl.kr[1][s4], qh, sc[1][hb]);
         if (QSPLIT) {
           const u32x4 ql = qs[QOPS + (hb * 4 + s4) * 64 + lane];
-          sc[0][hb] = mfma16(kr[0][s4], ql, sc[0][hb]);
-          sc[1][hb] = mfma16(kr[1][s4], ql, sc[1][hb]);
+          sc[0][hb] = mfma16(tl.kr[0][s4], ql, sc[0][hb]);
+          sc[1][hb] = mfma16(tl.kr[1][s4], ql, sc[1][hb]);
         }
       }
     }
-    load_k(tn);                 // K registers are free: fetch the wave's next tile
+    load_k(tl, tn, more);       // K registers are free: fetch the tile that will use them next
+    if (t == wave) MQA_STAMP(3);
 
     if (tail) {                 // ragged end of the range: drop positions >= end
 #pragma unroll
@@ -214,7 +238,7 @@ void decode_mfma_kernel(DecodeParams p) {
           }
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        if (p0 + 4 * e + g >= end) vr[e] = u32x4{0u, 0u, 0u, 0u};
+        if (p0 + 4 * e + g >= end) tl.vr[e] = u32x4{0u, 0u, 0u, 0u};
     }
 
     // ---- online softmax per head block; weights packed as MFMA B operands
@@ -264,7 +288,7 @@ void decode_mfma_kernel(DecodeParams p) {
         u32x4 a;
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-          a[x] = __builtin_amdgcn_perm(vr[2 * x + 1][w], vr[2 * x][w], par ? 0x07060302u : 0x05040100u);
+          a[x] = __builtin_amdgcn_perm(tl.vr[2 * x + 1][w], tl.vr[2 * x][w], par ? 0x07060302u : 0x05040100u);
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb) {
           acc[hb][j] = mfma16(a, phi[hb], acc[hb][j]);
@@ -272,8 +296,11 @@ void decode_mfma_kernel(DecodeParams p) {
         }
       }
     }
-    load_v(tn);
-  }
+    load_v(tl, tn, more);
+    if (t == wave) MQA_STAMP(4);
+  };
+  for (int t = wave; t < ntiles; t += NW) process(tb, t, t + NW);
+  MQA_STAMP(5);
 
   // ---- merge the NW wave states through LDS (re-using the q region)
 #pragma unroll
@@ -331,6 +358,7 @@ void decode_mfma_kernel(DecodeParams p) {
       }
     }
   }
+  MQA_STAMP(6);
 }
 
 template <int HB, int NW>
@@ -349,10 +377,15 @@ hipError_t launch_hb(const DecodeParams& p, int flags, hipStream_t st) {
     default: kern = MQA_PICK(false, false); break;
   }
 #undef MQA_PICK
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+  if (lds > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per kernel variant
+    static bool done[16] = {};
+    const int slot = (flags & 7);
+    if (!done[slot]) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      done[slot] = true;
+    }
   }
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);
   return hipGetLastError();

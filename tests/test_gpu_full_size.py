@@ -1,0 +1,108 @@
+"""Parity at the full workload sizes, in the launch configuration the benchmark
+times (library heuristics, no tuning).  The oracle cannot produce every output
+at these sizes in seconds, so sampled sequences / heads are compared element by
+element and cheap properties are checked on everything."""
+import numpy as np
+import pytest
+import torch
+
+import mqa_inputs as mi
+from oracle import mqa_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_1911_02150_amd as lib
+    lib.load_library()
+    return lib
+
+
+def _tol_bf16(got, ref, what):
+    err = float(np.max(np.abs(got - ref)))
+    assert np.isfinite(got).all(), what
+    assert err <= 2e-2 and err <= 1e-2 * float(np.max(np.abs(ref))), f"{what}: max abs err {err:.3e}"
+    return err
+
+
+def test_long_context_probe_mqa_full_size(m):
+    """b=64, m=8192, h=32, k=v=128, bf16 K/V, all lengths full (268 MB of K/V)."""
+    cfg = mi.CONFIGS[4]
+    b, h, cap, k, v = cfg["b"], cfg["h"], cfg["cap"], cfg["k"], cfg["v"]
+    q_np = mi.config4_q(b, h, k)
+    K_np, V_np = mi.config4_kv(b=b, m=cap, k=k, v=v, threads=8)
+    q = torch.from_numpy(q_np).to(DEV)
+    K, V = mi.bits_to_torch_bf16(K_np).to(DEV), mi.bits_to_torch_bf16(V_np).to(DEV)
+    lens = torch.full((b,), cap, dtype=torch.int32, device=DEV)
+    assert m.mqa_decode_num_splits(b, h, cap, k, v, m.MQA_BF16) == 4
+    o = m.mqa_decode_step(q, K, V, lens)
+    torch.cuda.synchronize()
+    got = o.cpu().numpy().astype(np.float64)
+    sample = [0, 1, 17, 31, 32, 47, 62, 63]
+    ref = orc.mqa_decode(q_np[sample], mi.bf16_bits_to_f64(K_np[sample]), mi.bf16_bits_to_f64(V_np[sample]),
+                         [cap] * len(sample))
+    err = _tol_bf16(got[sample], ref, "long-context probe, sampled sequences")
+    # every output is a convex combination of its sequence's V rows
+    Vf = V.float()
+    assert bool((o <= Vf.amax(dim=1)[:, None, :] + 1e-4).all()) and bool((o >= Vf.amin(dim=1)[:, None, :] - 1e-4).all())
+    assert np.isfinite(got).all()
+    print(f"long-context probe MQA: max abs err on {len(sample)} sequences {err:.2e}")
+
+
+def test_long_context_probe_mha_full_size(m):
+    """The multi-head twin: K, V [64,32,8192,128] bf16, 8 GiB.  The blocks K[i,j], V[i,j] are
+    copies of 8 seeded host-generated blocks (block (i*h+j) % 8), so any (i,j) output can be
+    checked against the oracle at the cost of one [8192,128] block."""
+    cfg = mi.CONFIGS[4]
+    b, h, cap, k, v = cfg["b"], cfg["h"], cfg["cap"], cfg["k"], cfg["v"]
+    npool = 8
+    pool = [mi.config4_kv_mh_block(0, p_, m=cap, k=k, v=v) for p_ in range(npool)]
+    Kp = torch.stack([mi.bits_to_torch_bf16(kb) for kb, _ in pool]).to(DEV)
+    Vp = torch.stack([mi.bits_to_torch_bf16(vb) for _, vb in pool]).to(DEV)
+    K = torch.empty((b, h, cap, k), dtype=torch.bfloat16, device=DEV)
+    V = torch.empty((b, h, cap, v), dtype=torch.bfloat16, device=DEV)
+    idx = (torch.arange(b * h, device=DEV) % npool).view(b, h)
+    for i in range(b):
+        K[i].copy_(Kp[idx[i]])
+        V[i].copy_(Vp[idx[i]])
+    q_np = mi.config4_q(b, h, k)
+    q = torch.from_numpy(q_np).to(DEV)
+    lens = torch.full((b,), cap, dtype=torch.int32, device=DEV)
+    o = m.mha_decode_step(q, K, V, lens)
+    torch.cuda.synchronize()
+    got = o.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    pairs = [(0, 0), (0, 31), (63, 0), (63, 31)] + [(int(i), int(j)) for i, j in
+                                                    zip(mi.rng(4, 999).integers(0, b, 60), mi.rng(4, 998).integers(0, h, 60))]
+    worst = 0.0
+    for i, j in pairs:
+        kb, vb = pool[(i * h + j) % npool]
+        ref = orc.dot_product_attention(q_np[i, j], mi.bf16_bits_to_f64(kb), mi.bf16_bits_to_f64(vb))
+        worst = max(worst, _tol_bf16(got[i, j], ref, f"mha (i,j)=({i},{j})"))
+    print(f"long-context probe MHA: max abs err on {len(pairs)} (sequence, head) pairs {worst:.2e}")
+
+
+def test_ragged_large_batch_full_size(m):
+    """b=512, h=64, cap=4096, lens ~ U[1,4096], 1 % of the logits lifted by +30, NaN beyond the lengths."""
+    cfg = mi.CONFIGS[5]
+    b, h, cap, k, v = cfg["b"], cfg["h"], cfg["cap"], cfg["k"], cfg["v"]
+    q_np, K_np, V_np, lens_np = mi.config5(b, h, k, v, cap, cfg["outlier_fraction"], cfg["outlier_boost"])
+    q = torch.from_numpy(q_np).to(DEV)
+    K, V = mi.bits_to_torch_bf16(K_np).to(DEV), mi.bits_to_torch_bf16(V_np).to(DEV)
+    lens = torch.from_numpy(lens_np).to(DEV)
+    o = m.mqa_decode_step(q, K, V, lens)
+    torch.cuda.synchronize()
+    got = o.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all(), "NaN rows beyond the length leaked into the output"
+    order = np.argsort(lens_np)
+    sample = sorted(set([int(order[0]), int(order[1]), int(order[-1]), int(order[-2]), int(order[b // 2])]
+                        + [int(x) for x in mi.rng(5, 999).integers(0, b, 7)]))
+    ref = orc.mqa_decode(q_np[sample], mi.bf16_bits_to_f64(K_np[sample]), mi.bf16_bits_to_f64(V_np[sample]),
+                         lens_np[sample])
+    err = _tol_bf16(got[sample], ref, "ragged batch, sampled sequences")
+    # the forced-large logits are present in the sample: some softmax rows are sharply peaked
+    w = orc.mqa_decode_weights(q_np[sample[-1:]], mi.bf16_bits_to_f64(K_np[sample[-1:]]), lens_np[sample[-1:]])[0]
+    print(f"ragged batch: lens {lens_np.min()}..{lens_np.max()}, max abs err on {len(sample)} sequences {err:.2e}, "
+          f"largest single weight in one sampled sequence {w.max():.3f}")
