@@ -46,6 +46,8 @@ namespace mqa {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float floatx4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) float floatx2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 namespace {
 
@@ -65,14 +67,22 @@ template <bool NTL> __device__ __forceinline__ u32x4 ld16(const u32x4* p) {
   return *p;
 }
 
-// hi/lo bf16 split of 8 floats -> two packed operands
+// two floats -> packed bf16 pair (round to nearest even; one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(floatx2{a, b}, bf16x2));
+}
+// hi + lo bf16 terms of a pair: hi = rne(x), lo = rne(x - hi) (the difference is exact in float32)
+__device__ __forceinline__ void split_pair(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = pack_bf16(a, b);
+  lo = pack_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
 __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    uint32_t h0 = float_to_bf16_rne(x[2 * d]), h1 = float_to_bf16_rne(x[2 * d + 1]);
-    float r0 = x[2 * d] - bf16_bits_to_float(h0), r1 = x[2 * d + 1] - bf16_bits_to_float(h1);
-    hi[d] = h0 | (h1 << 16);
-    lo[d] = float_to_bf16_rne(r0) | (float_to_bf16_rne(r1) << 16);
+    uint32_t h, l;
+    split_pair(x[2 * d], x[2 * d + 1], h, l);
+    hi[d] = h;
+    lo[d] = l;
   }
 }
 
@@ -269,12 +279,13 @@ void decode_mfma_kernel(DecodeParams p) {
       l_run[hb] += sum;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        const uint32_t b0 = __float_as_uint(pe[2 * d]), b1 = __float_as_uint(pe[2 * d + 1]);
-        phi[hb][d] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);     // truncated hi halves
         if (PSPLIT) {
-          const float r0 = pe[2 * d] - __uint_as_float(b0 & 0xffff0000u);
-          const float r1 = pe[2 * d + 1] - __uint_as_float(b1 & 0xffff0000u);
-          plo[hb][d] = float_to_bf16_rne(r0) | (float_to_bf16_rne(r1) << 16);
+          uint32_t hh, ll;
+          split_pair(pe[2 * d], pe[2 * d + 1], hh, ll);
+          phi[hb][d] = hh;
+          plo[hb][d] = ll;
+        } else {
+          phi[hb][d] = pack_bf16(pe[2 * d], pe[2 * d + 1]);
         }
       }
     }
@@ -302,14 +313,17 @@ void decode_mfma_kernel(DecodeParams p) {
   for (int t = wave; t < ntiles; t += NW) process(tb, t, t + NW);
   MQA_STAMP(5);
 
-  // ---- merge the NW wave states through LDS (re-using the q region)
+  // ---- merge the NW wave states through LDS.  The merge buffers follow the q operands, so a
+  // wave that finishes early writes its state without waiting for the others (with 64 heads
+  // the two regions do not fit side by side and the buffers re-use the q region after a barrier).
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     l_run[hb] += __shfl_xor(l_run[hb], 16);
     l_run[hb] += __shfl_xor(l_run[hb], 32);
   }
-  __syncthreads();
-  float* so = reinterpret_cast<float*>(smem_raw);           // [NW][NH][kOPitch]
+  constexpr bool kAlias = HB > 2;
+  if (kAlias) __syncthreads();
+  float* so = reinterpret_cast<float*>(smem_raw + (kAlias ? 0 : QOPS * 16 * 2));   // [NW][NH][kOPitch]
   float* sm = so + NW * NH * kOPitch;                       // [NW][NH]
   float* sl = sm + NW * NH;                                 // [NW][NH]
 #pragma unroll
@@ -365,7 +379,7 @@ template <int HB, int NW>
 hipError_t launch_hb(const DecodeParams& p, int flags, hipStream_t st) {
   const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 2 * NW * 16 * HB) * sizeof(float);
-  const size_t lds = q_bytes > merge_bytes ? q_bytes : merge_bytes;
+  const size_t lds = HB > 2 ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
   const dim3 grid((unsigned)((size_t)p.nseq * p.S * p.HG)), block(NW * 64);
   void (*kern)(DecodeParams);
   const bool ntl = !(flags & 4);
