@@ -157,6 +157,12 @@ void decode_mfma_kernel(DecodeParams p) {
       qb[it] = src[1];
     }
   }
+  // All waves of the workgroup put their q requests into the CU's memory queue before any of
+  // them queues its 16 KiB of K/V (plain s_barrier: no wait for the data), so q is not stuck
+  // behind the other waves' tiles and can be converted while the tiles stream in.
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   {
     const bool real = begin + 32 * wave <= rmax;
     load_k(tb, wave, real);
