@@ -64,8 +64,10 @@ typedef struct {
   int32_t splits;   /* >0: number of position ranges each sequence is split into */
   int32_t kernel;   /* 0 auto, 1 force the generic kernel, 2 force the MFMA kernel
                        (MQA_ERR_SHAPE if the shape does not qualify)             */
-  int32_t flags;    /* bit 0: single bf16 term for q; bit 1: single bf16 term for
-                       the softmax weights (faster, less accurate); 0 = default  */
+  int32_t flags;    /* MFMA kernel variants, 0 = default.  bit 0: single bf16 term for
+                       q; bit 1: single bf16 term for the softmax weights (both
+                       faster, less accurate); bit 2: plain instead of
+                       non-temporal cache loads; bit 4: 8 waves per workgroup   */
 } mqa_tuning;
 
 /*

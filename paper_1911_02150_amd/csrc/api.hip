@@ -28,7 +28,7 @@ int plan_decode(int nseq, int G, int cap, int k, int v, int is_bf16, const Tunin
   if (tn.kernel == 2 && !ok) return MQA_ERR_SHAPE;
   pl->use_mfma = ok && tn.kernel != 1;
   pl->HG = 1;
-  if (pl->use_mfma) pl->HG = (G + 16 * mfma_head_blocks(G) - 1) / (16 * mfma_head_blocks(G));
+  if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G) - 1) / mfma_heads_per_block(G);
   const int min_chunk = pl->use_mfma ? 128 : 256;
   int max_s = (cap + min_chunk - 1) / min_chunk;
   if (max_s > kMaxSplits) max_s = kMaxSplits;

@@ -27,6 +27,7 @@ struct DecodeParams {
   int chunk;             // positions per range (multiple of 32)
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
+  int merge_alias;       // MFMA kernel: 1 = the wave-merge buffers re-use the q operands' LDS
   float qscale;          // scale * log2(e): logits are kept in the log2 domain
 #ifdef MQA_TIMELINE
   long long* timeline;   // debug builds only: [waves][8] wall-clock stamps
@@ -39,9 +40,9 @@ struct Tuning {
   int flags = 0;
 };
 
-// decode_mfma.hip: bf16 cache, k = v = 128.  hb = head blocks of 16 (1, 2 or 4).
+// decode_mfma.hip: bf16 cache, k = v = 128; 16 or 32 heads per workgroup.
 bool mfma_shape_ok(int G, int k, int v, int is_bf16);
-int mfma_head_blocks(int G);
+int mfma_heads_per_block(int G);
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
 
 // decode_generic.hip: any k, v <= 256, float32 or bf16 cache.

@@ -6,7 +6,11 @@
 //   logits[j,p] = sum_c q[j,c] K[p,c];  weights = softmax_p;  o[j,:] = sum_p weights[j,p] V[p,:]
 //
 // Work decomposition
-//   grid  = nseq * S * HG workgroups (sequence, position range, group of 16*HB heads)
+//   grid  = nseq * S * HG workgroups (sequence, position range, group of 16*HB heads; HB = 1 or 2).
+//           More than 32 heads are split into head groups: the groups of one (sequence, range)
+//           are neighbouring work items on one XCD and read the same tiles at about the same
+//           time, so with cacheable loads the second read is served by L2.  (One wave holding
+//           64 heads spills, and two teams of waves in one workgroup measured slower.)
 //   block = NW independent wavefronts; wave w takes the 32-position tiles
 //           w, w+NW, ... of the range, so the block streams its range front to back.
 //   Each wave keeps, for all 16*HB heads, a running maximum, a running sum and
@@ -93,7 +97,7 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
 #endif
 
 template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL>
-__global__ __launch_bounds__(NW * 64, (HB <= 2 ? 2 : 1))
+__global__ __launch_bounds__(NW * 64, 2)
 void decode_mfma_kernel(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -319,17 +323,17 @@ void decode_mfma_kernel(DecodeParams p) {
   for (int t = wave; t < ntiles; t += NW) process(tb, t, t + NW);
   MQA_STAMP(5);
 
-  // ---- merge the NW wave states through LDS.  The merge buffers follow the q operands, so a
-  // wave that finishes early writes its state without waiting for the others (with 64 heads
-  // the two regions do not fit side by side and the buffers re-use the q region after a barrier).
+  // ---- merge the NW wave states through LDS.  When one workgroup per CU is all that runs, the
+  // merge buffers follow the q operands and a wave that finishes early writes its state without
+  // waiting for the others; when several workgroups should share a CU the buffers re-use the
+  // q region (after a barrier), which halves the LDS footprint.
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     l_run[hb] += __shfl_xor(l_run[hb], 16);
     l_run[hb] += __shfl_xor(l_run[hb], 32);
   }
-  constexpr bool kAlias = HB > 2;
-  if (kAlias) __syncthreads();
-  float* so = reinterpret_cast<float*>(smem_raw + (kAlias ? 0 : QOPS * 16 * 2));   // [NW][NH][kOPitch]
+  if (p.merge_alias) __syncthreads();
+  float* so = reinterpret_cast<float*>(smem_raw + (p.merge_alias ? 0 : QOPS * 16 * 2));   // [NW][NH][kOPitch]
   float* sm = so + NW * NH * kOPitch;                       // [NW][NH]
   float* sl = sm + NW * NH;                                 // [NW][NH]
 #pragma unroll
@@ -382,13 +386,17 @@ void decode_mfma_kernel(DecodeParams p) {
 }
 
 template <int HB, int NW>
-hipError_t launch_hb(const DecodeParams& p, int flags, hipStream_t st) {
+hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
+  DecodeParams p = p_in;
+  const size_t nblocks = (size_t)p.nseq * p.S * p.HG;
+  p.merge_alias = nblocks > 256 ? 1 : 0;      // more workgroups than CUs: keep LDS small
   const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 2 * NW * 16 * HB) * sizeof(float);
-  const size_t lds = HB > 2 ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
-  const dim3 grid((unsigned)((size_t)p.nseq * p.S * p.HG)), block(NW * 64);
+  const size_t lds = p.merge_alias ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
+  const dim3 grid((unsigned)nblocks), block(NW * 64);
   void (*kern)(DecodeParams);
-  const bool ntl = !(flags & 4);
+  // Non-temporal loads unless the tiles are meant to be found in L2 by a second head group.
+  const bool ntl = !(flags & 4) && p.HG == 1;
 #define MQA_PICK(QS, PS) (ntl ? decode_mfma_kernel<HB, NW, QS, PS, true> : decode_mfma_kernel<HB, NW, QS, PS, false>)
   switch (flags & 3) {
     case 0: kern = MQA_PICK(true, true); break;
@@ -397,12 +405,12 @@ hipError_t launch_hb(const DecodeParams& p, int flags, hipStream_t st) {
     default: kern = MQA_PICK(false, false); break;
   }
 #undef MQA_PICK
-  if (lds > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per kernel variant
-    static bool done[16] = {};
-    const int slot = (flags & 7);
+  if (q_bytes + merge_bytes > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per kernel variant
+    static bool done[8] = {};
+    const int slot = (flags & 3) | (ntl ? 4 : 0);
     if (!done[slot]) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(q_bytes + merge_bytes));
       if (e != hipSuccess) return e;
       done[slot] = true;
     }
@@ -418,15 +426,12 @@ bool mfma_shape_ok(int G, int k, int v, int is_bf16) {
   return is_bf16 && k == kD && v == kD;
 }
 
-int mfma_head_blocks(int G) { return G <= 16 ? 1 : (G <= 32 ? 2 : 4); }
+int mfma_heads_per_block(int G) { return G <= 16 ? 16 : 32; }
 
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
   const bool wide = (flags & 16) != 0;       // 8 waves per workgroup instead of 4
-  switch (mfma_head_blocks(p.G)) {
-    case 1: return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
-    case 2: return wide ? launch_hb<2, 8>(p, flags, st) : launch_hb<2, 4>(p, flags, st);
-    default: return launch_hb<4, 4>(p, flags, st);
-  }
+  if (mfma_heads_per_block(p.G) == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
+  return wide ? launch_hb<2, 8>(p, flags, st) : launch_hb<2, 4>(p, flags, st);
 }
 
 }  // namespace mqa
