@@ -157,6 +157,24 @@ int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int
 int mqa_stream_read(const void* src, size_t bytes, float* sink, void* stream);
 int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/*
+ * Glue of the benchmark's decoder-only stack (pre-layernorm residual blocks, ReLU feed-forward,
+ * tied token embedding: the model family of Section 4.1), so that a whole decoding loop runs in
+ * this library.  Not part of the attention path.  All float32, row-major, device pointers.
+ *   layernorm: y[r,:] = (x[r,:] - mean) / sqrt(var + eps), gain 1, bias 0 (biased variance)
+ *   embed:     x[r,:] = E[tokens[r],:] + P[positions[r],:]
+ *   add:       a[i] += b[i];      relu: a[i] = max(a[i], 0)
+ *   argmax:    out[r] = index of the largest x[r,:], the lowest index among equals
+ * The feed-forward and the output logits are mqa_project_qkvo calls (KV mode for x.W with
+ * W [d,n]; O mode with h = 1 for x.E^T with E [vocab,d]).
+ */
+int mqa_stack_layernorm(const float* x, float* y, int rows, int d, float eps, void* stream);
+int mqa_stack_embed(const int32_t* tokens, const int32_t* positions, const float* E, const float* P, float* x,
+                    int rows, int d, void* stream);
+int mqa_stack_add(float* a, const float* b, size_t n, void* stream);
+int mqa_stack_relu(float* a, size_t n, void* stream);
+int mqa_stack_argmax(const float* x, int32_t* out, int rows, int n, void* stream);
+
 const char* mqa_status_string(int status);
 
 #ifdef __cplusplus

@@ -20,6 +20,7 @@ EXPORTS = [
     "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
+    "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
 ]
 
 
@@ -63,6 +64,11 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_decode_num_splits.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp]
     lib.mqa_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mqa_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.mqa_stack_layernorm.argtypes = [vp, vp, ci, ci, cf, vp]
+    lib.mqa_stack_embed.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp]
+    lib.mqa_stack_add.argtypes = [vp, vp, sz, vp]
+    lib.mqa_stack_relu.argtypes = [vp, sz, vp]
+    lib.mqa_stack_argmax.argtypes = [vp, vp, ci, ci, vp]
     lib.mqa_status_string.argtypes = [ci]
     lib.mqa_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -253,3 +259,51 @@ def mqa_stream_copy(src, dst, stream=None):
     rc = lib.mqa_stream_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream))
     if rc != 0:
         raise MqaError("mqa_stream_copy", rc)
+
+
+def _rc(name, rc):
+    if rc != 0:
+        raise MqaError(name, rc)
+
+
+def mqa_stack_layernorm(x, out=None, eps=1e-6, stream=None):
+    _check(x, "x", torch.float32)
+    if out is None:
+        out = torch.empty_like(x)
+    rows, d = x.shape
+    _rc("mqa_stack_layernorm", load_library().mqa_stack_layernorm(_ptr(x), _ptr(out), rows, d, float(eps), _stream(stream)))
+    return out
+
+
+def mqa_stack_embed(tokens, positions, E, P, out=None, stream=None):
+    _check(tokens, "tokens", torch.int32), _check(positions, "positions", torch.int32)
+    _check(E, "E", torch.float32), _check(P, "P", torch.float32)
+    rows, d = tokens.numel(), E.shape[1]
+    if out is None:
+        out = torch.empty((rows, d), dtype=torch.float32, device=E.device)
+    _rc("mqa_stack_embed", load_library().mqa_stack_embed(_ptr(tokens), _ptr(positions), _ptr(E), _ptr(P), _ptr(out),
+                                                        rows, d, _stream(stream)))
+    return out
+
+
+def mqa_stack_add(a, b, stream=None):
+    _check(a, "a", torch.float32), _check(b, "b", torch.float32)
+    if a.numel() != b.numel():
+        raise ValueError("size mismatch in mqa_stack_add")
+    _rc("mqa_stack_add", load_library().mqa_stack_add(_ptr(a), _ptr(b), a.numel(), _stream(stream)))
+    return a
+
+
+def mqa_stack_relu(a, stream=None):
+    _check(a, "a", torch.float32)
+    _rc("mqa_stack_relu", load_library().mqa_stack_relu(_ptr(a), a.numel(), _stream(stream)))
+    return a
+
+
+def mqa_stack_argmax(x, out=None, stream=None):
+    _check(x, "x", torch.float32)
+    rows, n = x.shape
+    if out is None:
+        out = torch.empty((rows,), dtype=torch.int32, device=x.device)
+    _rc("mqa_stack_argmax", load_library().mqa_stack_argmax(_ptr(x), _ptr(out), rows, n, _stream(stream)))
+    return out

@@ -227,6 +227,38 @@ int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
 void mqa_debug_timeline(long long* p) { g_timeline = p; }
 #endif
 
+int mqa_stack_layernorm(const float* x, float* y, int rows, int d, float eps, void* stream) {
+  if (!x || !y) return MQA_ERR_NULL;
+  if (rows <= 0 || d <= 0) return MQA_ERR_SHAPE;
+  return launch_layernorm(x, y, rows, d, eps, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+int mqa_stack_embed(const int32_t* tokens, const int32_t* positions, const float* E, const float* P, float* x,
+                    int rows, int d, void* stream) {
+  if (!tokens || !positions || !E || !P || !x) return MQA_ERR_NULL;
+  if (rows <= 0 || d <= 0) return MQA_ERR_SHAPE;
+  return launch_embed(tokens, positions, E, P, x, rows, d, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+int mqa_stack_add(float* a, const float* b, size_t n, void* stream) {
+  if (!a || !b) return MQA_ERR_NULL;
+  if (n == 0) return MQA_ERR_SHAPE;
+  return launch_add(a, b, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+int mqa_stack_relu(float* a, size_t n, void* stream) {
+  if (!a) return MQA_ERR_NULL;
+  if (n == 0) return MQA_ERR_SHAPE;
+  return launch_relu(a, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
+int mqa_stack_argmax(const float* x, int32_t* out, int rows, int n, void* stream) {
+  if (!x || !out) return MQA_ERR_NULL;
+  if (rows <= 0 || n <= 0) return MQA_ERR_SHAPE;
+  return launch_argmax(x, out, rows, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
+}
+
 const char* mqa_status_string(int status) {
   switch (status) {
     case MQA_OK: return "ok";

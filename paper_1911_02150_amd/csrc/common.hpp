@@ -59,6 +59,14 @@ hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStrea
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, hipStream_t st);
 
+// stack_kernels.hip
+hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps, hipStream_t st);
+hipError_t launch_embed(const int32_t* tokens, const int32_t* pos, const float* E, const float* P, float* x,
+                        int rows, int d, hipStream_t st);
+hipError_t launch_add(float* a, const float* b, size_t n, hipStream_t st);
+hipError_t launch_relu(float* a, size_t n, hipStream_t st);
+hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStream_t st);
+
 // ---------------------------------------------------------------- device helpers
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);

@@ -1,0 +1,108 @@
+// Small kernels around the attention step of a decoder-only stack (pre-layernorm residual
+// blocks with a ReLU feed-forward, tied token embedding; the model family of the paper's
+// Section 4.1).  They exist so that the whole incremental decoding loop of the benchmark
+// stack runs in this library; the attention itself is in decode_*.hip and project.hip.
+// All float32; one workgroup (256 threads) per row.
+#include "common.hpp"
+
+namespace mqa {
+namespace {
+
+__device__ __forceinline__ float block_sum(float x, float* red) {
+  x = wave_sum(x);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wave] = x;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// y = (x - mean) / sqrt(var + eps), gain 1, bias 0 (biased variance over the row)
+__global__ __launch_bounds__(256)
+void layernorm_kernel(const float* __restrict__ x, float* __restrict__ y, int d, float eps) {
+  __shared__ float red[4];
+  const float* xr = x + (size_t)blockIdx.x * d;
+  float* yr = y + (size_t)blockIdx.x * d;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += xr[i];
+  const float mean = block_sum(s, red) / d;
+  float q = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float c = xr[i] - mean;
+    q += c * c;
+  }
+  const float rstd = 1.0f / sqrtf(block_sum(q, red) / d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) yr[i] = (xr[i] - mean) * rstd;
+}
+
+// x[row] = E[token[row]] + P[pos[row]]
+__global__ __launch_bounds__(256)
+void embed_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ pos,
+                  const float* __restrict__ E, const float* __restrict__ P, float* __restrict__ x, int d) {
+  const float* e = E + (size_t)tokens[blockIdx.x] * d;
+  const float* pp = P + (size_t)pos[blockIdx.x] * d;
+  float* xr = x + (size_t)blockIdx.x * d;
+  for (int i = threadIdx.x; i < d; i += 256) xr[i] = e[i] + pp[i];
+}
+
+// a += b   /   a = max(a, 0)
+__global__ __launch_bounds__(256)
+void add_kernel(float* __restrict__ a, const float* __restrict__ b, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) a[i] += b[i];
+}
+__global__ __launch_bounds__(256)
+void relu_kernel(float* __restrict__ a, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) a[i] = fmaxf(a[i], 0.f);
+}
+
+// out[row] = index of the largest element of the row, the lowest index among equals
+__global__ __launch_bounds__(256)
+void argmax_kernel(const float* __restrict__ x, int32_t* __restrict__ out, int n) {
+  __shared__ float sv[256];
+  __shared__ int si[256];
+  const float* xr = x + (size_t)blockIdx.x * n;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    const float v = xr[i];
+    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+  }
+  sv[threadIdx.x] = best;
+  si[threadIdx.x] = bi;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) {
+      const float v = sv[threadIdx.x + s];
+      const int j = si[threadIdx.x + s];
+      if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && j < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = j; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = si[0];
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(256), 0, st, x, y, d, eps);
+  return hipGetLastError();
+}
+hipError_t launch_embed(const int32_t* tokens, const int32_t* pos, const float* E, const float* P, float* x,
+                        int rows, int d, hipStream_t st) {
+  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(256), 0, st, tokens, pos, E, P, x, d);
+  return hipGetLastError();
+}
+hipError_t launch_add(float* a, const float* b, size_t n, hipStream_t st) {
+  hipLaunchKernelGGL(add_kernel, dim3((unsigned)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048)), dim3(256), 0, st, a, b, n);
+  return hipGetLastError();
+}
+hipError_t launch_relu(float* a, size_t n, hipStream_t st) {
+  hipLaunchKernelGGL(relu_kernel, dim3((unsigned)((n + 1023) / 1024 < 2048 ? (n + 1023) / 1024 : 2048)), dim3(256), 0, st, a, n);
+  return hipGetLastError();
+}
+hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStream_t st) {
+  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(256), 0, st, x, out, n);
+  return hipGetLastError();
+}
+
+}  // namespace mqa

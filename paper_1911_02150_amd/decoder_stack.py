@@ -1,0 +1,77 @@
+"""Incremental decoding of a decoder-only stack whose attention is the library's
+multi-query (or multi-head) decode step.  Pure glue: every operation is a call
+into the HIP library; torch only holds the device buffers.
+
+Stack (the model family of the paper's Section 4.1, random weights): token
+embedding + learned positional embedding; per layer  x += Attn(LN(x)),
+x += relu(LN(x) W1) W2;  final LN; logits = x E^T (embedding tied to the output
+layer); no biases; layernorm gain 1, bias 0, eps 1e-6.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class DecoderStack:
+    def __init__(self, weights: dict, batch: int, cap: int, multi_head: bool, device="cuda:0",
+                 cache_dtype=torch.bfloat16):
+        dev = torch.device(device)
+        self.dev, self.b, self.cap, self.multi_head = dev, batch, cap, multi_head
+        self.E = torch.from_numpy(weights["E"]).to(dev)
+        self.pos = torch.from_numpy(weights["pos"]).to(dev)
+        self.layers = [{k: torch.from_numpy(v).to(dev) for k, v in lw.items()} for lw in weights["layers"]]
+        h, d, k = self.layers[0]["P_q"].shape
+        v = self.layers[0]["P_o"].shape[2]
+        self.h, self.d, self.k, self.v = h, d, k, v
+        kshape = (batch, h, cap, k) if multi_head else (batch, cap, k)
+        vshape = (batch, h, cap, v) if multi_head else (batch, cap, v)
+        self.K = [torch.zeros(kshape, dtype=cache_dtype, device=dev) for _ in self.layers]
+        self.V = [torch.zeros(vshape, dtype=cache_dtype, device=dev) for _ in self.layers]
+        self.lens = [torch.zeros(batch, dtype=torch.int32, device=dev) for _ in self.layers]
+
+    # -- pieces, so that a test can look between them
+    def embed(self, tokens: torch.Tensor, t: int) -> torch.Tensor:
+        positions = torch.full((self.b,), t, dtype=torch.int32, device=self.dev)
+        return B.mqa_stack_embed(tokens.to(torch.int32), positions, self.E, self.pos)
+
+    def attention_append(self, l: int, x: torch.Tensor):
+        """LN, projections of q and the new K/V rows, append.  Returns q and the float32 rows."""
+        w = self.layers[l]
+        hx = B.mqa_stack_layernorm(x)
+        q = B.mqa_project_qkvo(B.MQA_PROJ_Q, hx, w["P_q"])
+        mode = B.MQA_PROJ_KV_MH if self.multi_head else B.MQA_PROJ_KV
+        kn = B.mqa_project_qkvo(mode, hx, w["P_k"])
+        vn = B.mqa_project_qkvo(mode, hx, w["P_v"])
+        B.mqa_append_kv(self.K[l], self.V[l], kn, vn, self.lens[l])
+        return q, kn, vn
+
+    def attention_attend(self, l: int, q: torch.Tensor) -> torch.Tensor:
+        """Attention over the cache and the output projection.  Returns y."""
+        dec = B.mha_decode_step if self.multi_head else B.mqa_decode_step
+        o = dec(q, self.K[l], self.V[l], self.lens[l])
+        return B.mqa_project_qkvo(B.MQA_PROJ_O, o, self.layers[l]["P_o"])
+
+    def feed_forward(self, l: int, x: torch.Tensor) -> torch.Tensor:
+        w = self.layers[l]
+        hx = B.mqa_stack_layernorm(x)
+        u = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["W1"])
+        B.mqa_stack_relu(u)
+        return B.mqa_project_qkvo(B.MQA_PROJ_KV, u, w["W2"])
+
+    def logits(self, x: torch.Tensor) -> torch.Tensor:
+        hx = B.mqa_stack_layernorm(x)
+        return B.mqa_project_qkvo(B.MQA_PROJ_O, hx.view(self.b, 1, self.d), self.E.view(1, -1, self.d))
+
+    # -- one decoding step for the whole stack
+    def step(self, tokens: torch.Tensor, t: int) -> torch.Tensor:
+        x = self.embed(tokens, t)
+        for l in range(len(self.layers)):
+            q, _, _ = self.attention_append(l, x)
+            B.mqa_stack_add(x, self.attention_attend(l, q))
+            B.mqa_stack_add(x, self.feed_forward(l, x))
+        return self.logits(x)
+
+    def greedy(self, logits: torch.Tensor) -> torch.Tensor:
+        return B.mqa_stack_argmax(logits)
