@@ -1,78 +1,133 @@
 // The four linear projections of the incremental listings (paper Section 2.4
 // and Section 3): q = einsum('bd,hdk->bhk'), the new K / V rows
 // einsum('bd,dk->bk') (multi-head: 'bd,hdk->bhk') and y = einsum('bhv,hdv->bd').
-// float32 in, float32 FMAs, float32 out.
+// float32 in, float32 products and accumulation on the matrix cores
+// (v_mfma_f32_32x32x2_f32), float32 out.
 //
 // All four are one GEMM out[rows, N] = in[rows, C] . B[C, N] with B addressed
 // inside the projection tensor P [h, d, kv]:
 //   Q / KV / KV_MH : C = d,    N = h*kv, B[t, n]  = P[n/kv][t][n%kv]   (N contiguous)
 //   O              : C = h*kv, N = d,    B[c, t]  = P[c/kv][t][c%kv]   (C contiguous)
-// Tiles of 32 rows x 64 columns, 32-deep slices through LDS, 2x4 outputs per thread.
+//
+// One workgroup of 8 waves per 32x32 (or, for small GEMMs, 16x16) output tile.  The
+// contraction axis is cut into groups of 4 chunks of 8 (16); wave w takes groups w, w+8, ... (one group in
+// flight while the previous one is multiplied) and the eight partial tiles are
+// summed through LDS.  With at most a few hundred rows these GEMMs are
+// bound by the fp32 matrix rate and by launch latency, not by HBM, so operands
+// are read straight from global memory (L2-resident) in MFMA layout:
+//   A operand: lane (i, kk) holds in[row0+i][c0 + 4kk + e], e = 0..3 (one 16-byte load),
+//              and MFMA e of the chunk contracts slots {c0+e, c0+4+e};
+//   B operand: lane (kk, j) holds B[c0 + 4kk + e][n0+j]: four 4-byte loads when N is
+//              contiguous, one 16-byte load when C is.
 #include "common.hpp"
 
 namespace mqa {
 namespace {
 
-constexpr int BM = 32, BN = 64, BK = 32, NT = 256;
+typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
 
-template <bool OUT_PROJ>
-__global__ __launch_bounds__(NT)
-void project_kernel(const float* __restrict__ in, const float* __restrict__ P, float* __restrict__ out,
-                    int rows, int d, int h, int kv) {
-  __shared__ float As[BK][BM + 4];
-  __shared__ float Bs[BK][BN + 4];
-  const int tid = threadIdx.x;
+constexpr int NWAVES = 8;
+constexpr int GC = 4;        // chunks of contraction indices fetched together
+
+// T = 32: 32x32 tiles (v_mfma_f32_32x32x2_f32, chunks of 8 contraction indices);
+// T = 16: 16x16 tiles (v_mfma_f32_16x16x4_f32, chunks of 16) for GEMMs too small to fill the
+// chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
+template <bool OUT_PROJ, int T>
+__global__ __launch_bounds__(NWAVES * 64)
+void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* __restrict__ out,
+                         int rows, int d, int h, int kv) {
+  constexpr int TM = T, TN = T;
+  constexpr int CH = 256 / T;                  // contraction indices per chunk (4 per lane group)
+  constexpr int NACC = T * T / 64;
+  __shared__ float red[NWAVES][TM * TN];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i32 = lane % T, kk = lane / T;
   const int C = OUT_PROJ ? h * kv : d;
   const int N = OUT_PROJ ? d : h * kv;
-  const int r0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int ty = tid >> 4, tx = tid & 15;
-  float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  const int row0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
   const size_t head_stride = (size_t)d * kv;
 
-  for (int c0 = 0; c0 < C; c0 += BK) {
-    {  // A slice: 32 rows x 32 contraction indices, one float4 per thread, stored transposed
-      const int row = tid >> 3, c4 = (tid & 7) * 4;
-      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r0 + row < rows && c0 + c4 < C)
-        a = *reinterpret_cast<const float4*>(in + (size_t)(r0 + row) * C + c0 + c4);
-      As[c4 + 0][row] = a.x; As[c4 + 1][row] = a.y; As[c4 + 2][row] = a.z; As[c4 + 3][row] = a.w;
-    }
+  // A: this lane's row (clamped; rows past the end are discarded at the store)
+  const float* arow = in + (size_t)min(row0 + i32, rows - 1) * C + 4 * kk;
+  // B: this lane's output column n = n0 + i32 (clamped likewise)
+  const int n = min(n0 + i32, N - 1);
+  const float* bcol;       // OUT_PROJ: contiguous along c;  else: element (t, n), stride kv along t
+  if (OUT_PROJ) bcol = P + (size_t)n * kv + 4 * kk;                      // + (c / kv) * head_stride + c % kv
+  else bcol = P + (size_t)(n / kv) * head_stride + (n % kv) + (size_t)(4 * kk) * kv;
+
+  typedef __attribute__((ext_vector_type(NACC))) float accv;
+  accv acc;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int idx = tid + i * NT;
-      if (!OUT_PROJ) {   // B[t, n]: float4 along n
-        const int kk = idx >> 4, n4 = (idx & 15) * 4;
-        const int t = c0 + kk, n = n0 + n4;
-        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (t < C && n < N)
-          b = *reinterpret_cast<const float4*>(P + (size_t)(n / kv) * head_stride + (size_t)t * kv + (n % kv));
-        *reinterpret_cast<float4*>(&Bs[kk][n4]) = b;
-      } else {           // B[c, t]: float4 along c, stored transposed
-        const int tt = idx >> 3, c4 = (idx & 7) * 4;
-        const int t = n0 + tt, c = c0 + c4;
-        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (t < N && c < C)
-          b = *reinterpret_cast<const float4*>(P + (size_t)(c / kv) * head_stride + (size_t)t * kv + (c % kv));
-        Bs[c4 + 0][tt] = b.x; Bs[c4 + 1][tt] = b.y; Bs[c4 + 2][tt] = b.z; Bs[c4 + 3][tt] = b.w;
+  for (int r = 0; r < NACC; ++r) acc[r] = 0.f;
+
+  const int nchunks = C / CH;                  // C is a multiple of 8; a last half chunk (T = 16) is handled below
+  const int tail = C - nchunks * CH;           // 0 or 8 (only when T = 16)
+  const int ngroups = (nchunks + (tail ? 1 : 0) + GC - 1) / GC;
+  auto load_group = [&](int grp, float4 (&a)[GC], float4 (&b)[GC]) {
+#pragma unroll
+    for (int e = 0; e < GC; ++e) {
+      const int chunk = grp * GC + e;
+      // the last, half-filled chunk of a 16-wide contraction: only lane groups kk < 2 hold data
+      if (chunk < nchunks || (chunk == nchunks && tail && kk < 2)) {
+        const int c0 = chunk * CH;
+        a[e] = *reinterpret_cast<const float4*>(arow + c0);
+        if (OUT_PROJ) {
+          const int c = c0 + 4 * kk;                 // 4 consecutive c stay inside one head (kv % 8 == 0)
+          b[e] = *reinterpret_cast<const float4*>(P + (size_t)(c / kv) * head_stride + (size_t)n * kv + (c % kv));
+        } else {
+          const float* bp = bcol + (size_t)c0 * kv;
+          b[e] = make_float4(bp[0], bp[kv], bp[2 * (size_t)kv], bp[3 * (size_t)kv]);
+        }
+      } else {
+        a[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+        b[e] = make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
-    __syncthreads();
+  };
+  auto multiply = [&](const float4 (&a)[GC], const float4 (&b)[GC]) {
 #pragma unroll
-    for (int kk = 0; kk < BK; ++kk) {
-      const float a0 = As[kk][2 * ty], a1 = As[kk][2 * ty + 1];
-      const float4 b = *reinterpret_cast<const float4*>(&Bs[kk][4 * tx]);
-      acc[0][0] = fmaf(a0, b.x, acc[0][0]); acc[0][1] = fmaf(a0, b.y, acc[0][1]);
-      acc[0][2] = fmaf(a0, b.z, acc[0][2]); acc[0][3] = fmaf(a0, b.w, acc[0][3]);
-      acc[1][0] = fmaf(a1, b.x, acc[1][0]); acc[1][1] = fmaf(a1, b.y, acc[1][1]);
-      acc[1][2] = fmaf(a1, b.z, acc[1][2]); acc[1][3] = fmaf(a1, b.w, acc[1][3]);
+    for (int e = 0; e < GC; ++e) {
+      if constexpr (T == 32) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].x, b[e].x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].y, b[e].y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].z, b[e].z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].w, b[e].w, acc, 0, 0, 0);
+      } else {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].x, b[e].x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].y, b[e].y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].z, b[e].z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].w, b[e].w, acc, 0, 0, 0);
+      }
     }
-    __syncthreads();
+  };
+
+  float4 a0[GC], b0[GC], a1[GC], b1[GC];
+  int grp = wave;
+  if (grp < ngroups) load_group(grp, a0, b0);
+  while (grp < ngroups) {
+    if (grp + NWAVES < ngroups) load_group(grp + NWAVES, a1, b1);
+    multiply(a0, b0);
+    grp += NWAVES;
+    if (grp >= ngroups) break;
+    if (grp + NWAVES < ngroups) load_group(grp + NWAVES, a0, b0);
+    multiply(a1, b1);
+    grp += NWAVES;
   }
+
+  // D layout: register r of lane (j, g) is tile element (8*(r/4) + 4*g + r%4, j) for the 32x32
+  // tile and (4*g + r, j) for the 16x16 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = r0 + 2 * ty + i, n = n0 + 4 * tx;
-    if (r < rows && n < N)
-      *reinterpret_cast<float4*>(out + (size_t)r * N + n) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+  for (int r = 0; r < NACC; ++r) {
+    const int trow = (T == 32) ? (8 * (r >> 2) + 4 * kk + (r & 3)) : (4 * kk + r);
+    red[wave][trow * TN + i32] = acc[r];
+  }
+  __syncthreads();
+  for (int e = tid; e < TM * TN; e += NWAVES * 64) {
+    const int r = e / TN, c = e % TN;
+    if (row0 + r < rows && n0 + c < N)
+      out[(size_t)(row0 + r) * N + n0 + c] = ((red[0][e] + red[1][e]) + (red[2][e] + red[3][e])) +
+                                             ((red[4][e] + red[5][e]) + (red[6][e] + red[7][e]));
   }
 }
 
@@ -82,11 +137,17 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, hipStream_t st) {
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
-  const dim3 grid((N + BN - 1) / BN, (rows + BM - 1) / BM), block(NT);
-  if (outp)
-    hipLaunchKernelGGL(project_kernel<true>, grid, block, 0, st, in, P, out, rows, d, h, kv);
-  else
-    hipLaunchKernelGGL(project_kernel<false>, grid, block, 0, st, in, P, out, rows, d, h, kv);
+  const long long tiles32 = (long long)((N + 31) / 32) * ((rows + 31) / 32);
+  const dim3 block(NWAVES * 64);
+  if (tiles32 >= 512) {          // enough 32x32 tiles for two workgroups per CU
+    const dim3 grid((N + 31) / 32, (rows + 31) / 32);
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+    else hipLaunchKernelGGL((project_mfma_kernel<false, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+  } else {
+    const dim3 grid((N + 15) / 16, (rows + 15) / 16);
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+    else hipLaunchKernelGGL((project_mfma_kernel<false, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+  }
   return hipGetLastError();
 }
 
