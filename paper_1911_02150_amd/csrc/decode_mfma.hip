@@ -327,15 +327,10 @@ void decode_mfma_kernel(DecodeParams p) {
   // merge buffers follow the q operands and a wave that finishes early writes its state without
   // waiting for the others; when several workgroups should share a CU the buffers re-use the
   // q region (after a barrier), which halves the LDS footprint.
-#pragma unroll
-  for (int hb = 0; hb < HB; ++hb) {
-    l_run[hb] += __shfl_xor(l_run[hb], 16);
-    l_run[hb] += __shfl_xor(l_run[hb], 32);
-  }
   if (p.merge_alias) __syncthreads();
   float* so = reinterpret_cast<float*>(smem_raw + (p.merge_alias ? 0 : QOPS * 16 * 2));   // [NW][NH][kOPitch]
-  float* sm = so + NW * NH * kOPitch;                       // [NW][NH]
-  float* sl = sm + NW * NH;                                 // [NW][NH]
+  float* sm = so + NW * NH * kOPitch;                       // [NW][NH]     running maxima
+  float* sl = sm + NW * NH;                                 // [NW][NH][4]  sums, one per lane group g
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     float* row = so + ((size_t)wave * NH + 16 * hb + i16) * kOPitch;
@@ -347,26 +342,41 @@ void decode_mfma_kernel(DecodeParams p) {
       dst[0] = lo4;
       dst[1] = hi4;
     }
-    if (g == 0) {
-      sm[wave * NH + 16 * hb + i16] = m_run[hb];
-      sl[wave * NH + 16 * hb + i16] = l_run[hb];
-    }
+    if (g == 0) sm[wave * NH + 16 * hb + i16] = m_run[hb];
+    sl[(wave * NH + 16 * hb + i16) * 4 + g] = l_run[hb];      // the four lanes of a head share one maximum
   }
   __syncthreads();
-  for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
+  constexpr int ITERS = NH * (kD / 4) / NT;                   // float4 outputs per thread
+  float fw[ITERS][NW], lw[ITERS][NW];
+  float4 xw[ITERS][NW];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {                        // all LDS reads first: one latency
+    const int idx = tid + it * NT;
+    const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      fw[it][w] = sm[w * NH + hl];
+      const float4 l4 = *reinterpret_cast<const float4*>(sl + (w * NH + hl) * 4);
+      lw[it][w] = (l4.x + l4.y) + (l4.z + l4.w);
+      xw[it][w] = reinterpret_cast<const float4*>(so + ((size_t)w * NH + hl) * kOPitch)[c4];
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int idx = tid + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
     if (head0 + hl >= p.G) continue;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) M = fmaxf(M, sm[w * NH + hl]);
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, fw[it][w]);
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     float lsum = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      const float f = __builtin_amdgcn_exp2f(sm[w * NH + hl] - M);   // wave 0 always has a tile: M finite
-      const float4 x = reinterpret_cast<const float4*>(so + ((size_t)w * NH + hl) * kOPitch)[c4];
+      const float f = __builtin_amdgcn_exp2f(fw[it][w] - M);   // wave 0 always has a tile: M finite
+      const float4 x = xw[it][w];
       a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
-      lsum += f * sl[w * NH + hl];
+      lsum += f * lw[it][w];
     }
     const int head = head0 + hl;
     if (p.S == 1) {
@@ -391,7 +401,7 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   const size_t nblocks = (size_t)p.nseq * p.S * p.HG;
   p.merge_alias = nblocks > 256 ? 1 : 0;      // more workgroups than CUs: keep LDS small
   const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
-  const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 2 * NW * 16 * HB) * sizeof(float);
+  const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 5 * NW * 16 * HB) * sizeof(float);
   const size_t lds = p.merge_alias ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
   const dim3 grid((unsigned)nblocks), block(NW * 64);
   void (*kern)(DecodeParams);
