@@ -344,3 +344,56 @@ def test_config2_free_running(m):
     ulp = 2.0 ** (np.floor(np.log2(np.max(np.abs(Vr)))) - 7)
     assert worst <= 2e-2 + ulp, worst
     print(f"config 2 free running: worst o err {worst:.2e} (bf16 ulp of max|V| = {ulp:.2e})")
+
+
+# ----------------------------------------------------------------- robustness of the boundary
+def test_lengths_outside_capacity_are_clamped(m):
+    """lens values outside [0, cap] are clamped by the kernels (the host cannot see them)."""
+    c = mi.random_case(50, 4, 8, 160, 128, 128, cache="bf16", lens="full", poison=False)
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.tensor([160, 1000, -5, 77], dtype=torch.int32, device=DEV)
+    for tuning in (dict(kernel=2), dict(kernel=2, splits=3), dict(kernel=1), dict(kernel=1, splits=2)):
+        o = m.mqa_decode_step(q, K, V, lens, tuning=tuning)
+        ref = orc.mqa_decode(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), [160, 160, 0, 77])
+        check(o, ref, "bf16", f"clamped lens {tuning}")
+        assert float(o[2].abs().max()) == 0.0
+
+
+def test_decode_step_in_a_hip_graph(m):
+    """The library neither allocates nor synchronises, so a whole step (append + attention)
+    can be captured in a HIP graph; every replay must equal the eager result."""
+    b, h, cap = 8, 32, 2048
+    c = mi.random_case(51, b, h, cap, 128, 128, cache="bf16", lens="ragged", poison=False)
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens0 = torch.from_numpy(np.minimum(c["lens"], cap - 8)).to(DEV)
+    g = mi.rng(1051, 3)
+    kn = torch.from_numpy(g.standard_normal((b, 128), dtype=np.float32)).to(DEV)
+    vn = torch.from_numpy(g.standard_normal((b, 128), dtype=np.float32)).to(DEV)
+    ws = torch.empty(m.mqa_decode_workspace_bytes(b, h, cap, 128), dtype=torch.uint8, device=DEV)
+    o = torch.empty((b, h, 128), dtype=torch.float32, device=DEV)
+
+    def eager(lens):
+        m.mqa_append_kv(K, V, kn, vn, lens)
+        return m.mqa_decode_step(q, K, V, lens, o=torch.empty_like(o), workspace=ws).clone()
+
+    lens = lens0.clone()
+    expect = [eager(lens) for _ in range(3)]            # three steps, each one position longer
+    K2, V2 = to_dev_cache(c["K"]), to_dev_cache(c["V"])  # fresh caches for the captured run
+    lens = lens0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            m.mqa_append_kv(K2, V2, kn, vn, lens, stream=side)
+            m.mqa_decode_step(q, K2, V2, lens, o=o, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    lens.copy_(lens0)                                    # the capture itself ran nothing
+    for i in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, expect[i]), f"replay {i} differs from the eager step"
+        _ = (q * 2).sum().item()                         # unrelated eager work between replays
+    assert torch.equal(lens, lens0 + 3)
