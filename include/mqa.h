@@ -117,7 +117,20 @@ int mha_decode_step(const float* q, const void* K, const void* V, const int32_t*
                     int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
                     void* workspace, size_t workspace_bytes, void* stream);
 
-/* Same as the two calls above with explicit launch tuning (NULL = defaults). */
+/*
+ * Local attention, the variant of the paper's Section 4.1 ("attention to the current position
+ * and the previous 31 positions"): as the two calls above, but sequence i attends only to
+ * positions [max(0, lens[i] - window), lens[i]).  window > 0 (32 in the paper).  Only the rows
+ * inside the window are read.
+ */
+int mqa_decode_step_window(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, int window,
+                           void* workspace, size_t workspace_bytes, void* stream);
+int mha_decode_step_window(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, int window,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same as mqa_decode_step / mha_decode_step with explicit launch tuning (NULL = defaults). */
 int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                        int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,
                        void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);

@@ -17,9 +17,10 @@ def softmax_list(z):
     return [t / s for t in e]
 
 
-def mqa_decode_bf(q, K, V, lens, scale=1.0):
+def mqa_decode_bf(q, K, V, lens, scale=1.0, window=None):
     """Section 3 step: q[b][h][k], K[b][m][k], V[b][m][v] nested lists ->
-    o[b][h][v]; sequence i uses its first lens[i] positions."""
+    o[b][h][v]; sequence i uses its first lens[i] positions, or only the last
+    `window` of them (the local variant of Section 4.1)."""
     b, h = len(q), len(q[0])
     kdim, vdim = len(q[0][0]), len(V[0][0])
     out = []
@@ -30,9 +31,10 @@ def mqa_decode_bf(q, K, V, lens, scale=1.0):
             if L == 0:
                 rows.append([0.0] * vdim)
                 continue
-            logits = [scale * math.fsum(q[i][j][c] * K[i][p][c] for c in range(kdim)) for p in range(L)]
+            lo = 0 if window is None else max(0, L - window)
+            logits = [scale * math.fsum(q[i][j][c] * K[i][p][c] for c in range(kdim)) for p in range(lo, L)]
             w = softmax_list(logits)
-            rows.append([math.fsum(w[p] * V[i][p][c] for p in range(L)) for c in range(vdim)])
+            rows.append([math.fsum(w[p - lo] * V[i][p][c] for p in range(lo, L)) for c in range(vdim)])
         out.append(rows)
     return out
 

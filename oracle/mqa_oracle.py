@@ -30,7 +30,8 @@ Readings taken where the paper's listings are silent or garbled:
 Parity pins (tests/test_oracle_*.py): brute-force enumeration on tiny shapes,
 softmax against scipy, weights sum to one, MQA == MHA with shared K/V,
 incremental == causally masked batched attention, closed forms (one position,
-zero query, dominant logit, shift and permutation invariance, convex hull),
+zero query, dominant logit, shift and permutation invariance, convex hull,
+a window as a shortened cache, a window of one position),
 torch float64 scaled-dot-product attention as an independent routine, split
 and recombine of the softmax state, NaN rows beyond the length, and bf16
 rounding against torch's cast.  No function here is "parity unpinned".
@@ -205,11 +206,13 @@ def mqa_decode_weights(q, K, lens, scale=1.0):
     return out
 
 
-def mqa_decode(q, K, V, lens, scale=1.0):
+def mqa_decode(q, K, V, lens, scale=1.0, window=None):
     """Attention part of `MultiquerySelfAttentionIncremental` (Section 3):
     logits = einsum('bhk,bmk->bhm'), softmax over m, o = einsum('bhm,bmv->bhv'),
     restricted per sequence to its first lens[i] positions.
-    q [b,h,k], K [b,cap,k], V [b,cap,v] -> o [b,h,v]."""
+    q [b,h,k], K [b,cap,k], V [b,cap,v] -> o [b,h,v].
+    `window` = W gives the "local" variant of Section 4.1: only the current position
+    and the W-1 before it, i.e. positions [max(0, lens[i]-W), lens[i])."""
     q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
     b, h, _ = q.shape
     o = np.zeros((b, h, V.shape[-1]), dtype=F64)
@@ -217,16 +220,17 @@ def mqa_decode(q, K, V, lens, scale=1.0):
         L = int(lens[i])
         if L == 0:
             continue
-        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, :L], optimize=True)
+        lo = 0 if window is None else max(0, L - int(window))
+        logits = scale * np.einsum("hk,mk->hm", q[i], K[i, lo:L], optimize=True)
         weights = softmax64(logits)
-        o[i] = np.einsum("hm,mv->hv", weights, V[i, :L], optimize=True)
+        o[i] = np.einsum("hm,mv->hv", weights, V[i, lo:L], optimize=True)
     return o
 
 
-def mha_decode(q, K, V, lens, scale=1.0):
+def mha_decode(q, K, V, lens, scale=1.0, window=None):
     """Attention part of `MultiheadSelfAttentionIncremental` (Section 2.4):
     logits = einsum('bhk,bhmk->bhm'), softmax, o = einsum('bhm,bhmv->bhv').
-    q [b,h,k], K [b,h,cap,k], V [b,h,cap,v] -> o [b,h,v]."""
+    q [b,h,k], K [b,h,cap,k], V [b,h,cap,v] -> o [b,h,v].  `window` as in mqa_decode."""
     q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
     b, h, _ = q.shape
     o = np.zeros((b, h, V.shape[-1]), dtype=F64)
@@ -234,9 +238,10 @@ def mha_decode(q, K, V, lens, scale=1.0):
         L = int(lens[i])
         if L == 0:
             continue
-        logits = scale * np.einsum("hk,hmk->hm", q[i], K[i, :, :L], optimize=True)
+        lo = 0 if window is None else max(0, L - int(window))
+        logits = scale * np.einsum("hk,hmk->hm", q[i], K[i, :, lo:L], optimize=True)
         weights = softmax64(logits)
-        o[i] = np.einsum("hm,hmv->hv", weights, V[i, :, :L], optimize=True)
+        o[i] = np.einsum("hm,hmv->hv", weights, V[i, :, lo:L], optimize=True)
     return o
 
 

@@ -17,7 +17,7 @@ MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
 
 EXPORTS = [
     "mqa_project_qkvo", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
-    "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
+    "mqa_decode_step_window", "mha_decode_step_window", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
@@ -53,6 +53,9 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
     lib.mqa_decode_step.argtypes = dec
     lib.mha_decode_step.argtypes = dec
+    win = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.mqa_decode_step_window.argtypes = win
+    lib.mha_decode_step_window.argtypes = win
     lib.mqa_decode_step_ex.argtypes = dec + [tp]
     lib.mha_decode_step_ex.argtypes = dec + [tp]
     lib.mqa_decode_partials.argtypes = dec + [tp]
@@ -143,7 +146,7 @@ def mqa_decode_num_splits(b, h, cap, k, v, dt, multi_head=False, tuning=None) ->
     return int(load_library().mqa_decode_num_splits(b, h, cap, k, v, dt, int(multi_head), _tuning(tuning)))
 
 
-def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tuning, with_tuning=True):
+def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tuning, with_tuning=True, window=None):
     lib = load_library()
     _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
     b, h, k = q.shape
@@ -160,8 +163,10 @@ def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tun
     if workspace is None:
         nbytes = mha_decode_workspace_bytes(b, h, cap, v) if multi_head else mqa_decode_workspace_bytes(b, h, cap, v)
         workspace = _default_workspace(q.device, nbytes)
-    args = [_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K), float(scale),
-            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
+    args = [_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K), float(scale)]
+    if window is not None:
+        args.append(int(window))
+    args += [_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)]
     if with_tuning:
         args.append(_tuning(tuning))
     rc = getattr(lib, fn_name)(*args)
@@ -182,6 +187,15 @@ def mha_decode_step(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=Non
     if tuning is None:
         return _decode("mha_decode_step", True, q, K, V, lens, o, scale, workspace, stream, None, False)
     return _decode("mha_decode_step_ex", True, q, K, V, lens, o, scale, workspace, stream, tuning)
+
+
+def mqa_decode_step_window(q, K, V, lens, window, o=None, scale=1.0, workspace=None, stream=None):
+    """Local attention: sequence i attends to its last `window` valid positions only."""
+    return _decode("mqa_decode_step_window", False, q, K, V, lens, o, scale, workspace, stream, None, False, window)
+
+
+def mha_decode_step_window(q, K, V, lens, window, o=None, scale=1.0, workspace=None, stream=None):
+    return _decode("mha_decode_step_window", True, q, K, V, lens, o, scale, workspace, stream, None, False, window)
 
 
 def mqa_decode_partials(q, K, V, lens, o, workspace, scale=1.0, stream=None, tuning=None):

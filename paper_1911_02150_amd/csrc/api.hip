@@ -23,7 +23,14 @@ struct Plan {
 
 // Split of the position axis.  Every range is a multiple of 32 positions; a
 // range is at least 128 (MFMA: one tile per wave) or 256 (generic) positions.
-int plan_decode(int nseq, int G, int cap, int k, int v, int is_bf16, const Tuning& tn, Plan* pl) {
+int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_bf16, const Tuning& tn, Plan* pl) {
+  // with a window a sequence attends to at most window positions, lying in at most
+  // ceil(window/32)+1 tiles counted from the 32-aligned start of the window
+  int cap = cap_all;
+  if (window > 0 && window < cap_all) {
+    const long long span = (((long long)window + 31) & ~31ll) + 32;
+    if (span < cap) cap = (int)span;
+  }
   const bool ok = mfma_shape_ok(G, k, v, is_bf16);
   if (tn.kernel == 2 && !ok) return MQA_ERR_SHAPE;
   pl->use_mfma = ok && tn.kernel != 1;
@@ -71,7 +78,8 @@ int check_decode_args(const float* q, const void* K, const void* V, const int32_
 int decode_impl(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                 int b, int h, int cap, int k, int v, int dt, float scale,
                 void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning,
-                bool multi_head, int phase) {
+                bool multi_head, int phase, int window = 0) {
+  if (window < 0) return MQA_ERR_SHAPE;
   int rc = check_decode_args(q, K, V, lens, o, b, h, cap, k, v, dt, (phase & 1) != 0);
   if (rc) return rc;
   Tuning tn;
@@ -83,7 +91,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   const int nseq = multi_head ? b * h : b;
   const int G = multi_head ? 1 : h;
   Plan pl;
-  rc = plan_decode(nseq, G, cap, k, v, dt == MQA_BF16, tn, &pl);
+  rc = plan_decode(nseq, G, cap, window, k, v, dt == MQA_BF16, tn, &pl);
   if (rc) return rc;
   if (pl.S > 1) {
     if (!workspace || workspace_bytes < partial_bytes(nseq, pl.S, G, v)) return MQA_ERR_WORKSPACE;
@@ -95,7 +103,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   p.part_m = p.part_o ? p.part_o + (size_t)nseq * pl.S * G * v : nullptr;
   p.part_l = p.part_m ? p.part_m + (size_t)nseq * pl.S * G : nullptr;
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
-  p.k = k; p.v = v; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
+  p.k = k; p.v = v; p.window = window; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
 #ifdef MQA_TIMELINE
   p.timeline = g_timeline;
@@ -128,6 +136,22 @@ int mha_decode_step(const float* q, const void* K, const void* V, const int32_t*
                     void* workspace, size_t workspace_bytes, void* stream) {
   return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
                      nullptr, true, 3);
+}
+
+int mqa_decode_step_window(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, int window,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (window <= 0) return MQA_ERR_SHAPE;
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, false, 3, window);
+}
+
+int mha_decode_step_window(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, int window,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (window <= 0) return MQA_ERR_SHAPE;
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, true, 3, window);
 }
 
 int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
@@ -178,7 +202,7 @@ int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int
     tn.flags = tuning->flags;
   }
   Plan pl;
-  const int rc = plan_decode(multi_head ? b * h : b, multi_head ? 1 : h, cap, k, v, dt == MQA_BF16, tn, &pl);
+  const int rc = plan_decode(multi_head ? b * h : b, multi_head ? 1 : h, cap, 0, k, v, dt == MQA_BF16, tn, &pl);
   return rc ? -rc : pl.S;
 }
 

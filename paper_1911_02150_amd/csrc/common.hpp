@@ -24,6 +24,7 @@ struct DecodeParams {
   float* part_l;         // [nseq, S, G]     sums of 2^(logit - max)
   int nseq, G, cap, lens_div;
   int k, v;
+  int window;            // > 0: attend only to the last `window` valid positions (0 = all)
   int chunk;             // positions per range (multiple of 32)
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
@@ -68,6 +69,10 @@ hipError_t launch_relu(float* a, size_t n, hipStream_t st);
 hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStream_t st);
 
 // ---------------------------------------------------------------- device helpers
+// First position a sequence of length L attends to, and the 32-aligned position its ranges start from.
+__device__ __forceinline__ int window_lo(int L, int window) { return window > 0 ? max(0, L - window) : 0; }
+__device__ __forceinline__ int window_base(int L, int window) { return window_lo(L, window) & ~31; }
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
 }

@@ -39,8 +39,10 @@ void decode_generic_kernel(DecodeParams p) {
   const int seq = blockIdx.x / p.S;
   int L = p.lens[seq / p.lens_div];
   L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-  const int begin = srange * p.chunk;
-  const int end = min(begin + p.chunk, L);
+  const int lo = window_lo(L, p.window);                    // local attention: positions [lo, L)
+  const int range0 = window_base(L, p.window) + srange * p.chunk;
+  const int begin = max(range0, lo);
+  const int end = min(range0 + p.chunk, L);
   if (end <= begin) {
     if (p.S == 1)
       for (int idx = tid; idx < p.G * v; idx += kThreads) p.o[(size_t)seq * p.G * v + idx] = 0.f;

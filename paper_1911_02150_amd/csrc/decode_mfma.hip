@@ -112,7 +112,7 @@ void decode_mfma_kernel(DecodeParams p) {
   const int srange = (wid / p.HG) % p.S;
   const int seq = wid / (p.HG * p.S);
   const int head0 = hg * NH;
-  const int begin = srange * p.chunk;          // < cap by construction of S and chunk
+  int begin = srange * p.chunk;                // < cap by construction of S and chunk; moved up below for a window
 
   const u32x4* Kbase = reinterpret_cast<const u32x4*>(p.K) + (size_t)seq * p.cap * kRowU4;
   const u32x4* Vbase = reinterpret_cast<const u32x4*>(p.V) + (size_t)seq * p.cap * kRowU4;
@@ -167,7 +167,7 @@ void decode_mfma_kernel(DecodeParams p) {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  {
+  if (p.window == 0) {
     const bool real = begin + 32 * wave <= rmax;
     load_k(tb, wave, real);
     load_v(tb, wave, real);
@@ -175,6 +175,15 @@ void decode_mfma_kernel(DecodeParams p) {
   MQA_STAMP(1);
   int L = p.lens[seq / p.lens_div];
   L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
+  // Local attention (the paper's Section 4.1 variant): only positions [lo, L) count; the ranges
+  // then start at the 32-aligned position below lo, which is known only now.
+  const int lo = window_lo(L, p.window);
+  if (p.window > 0) {
+    begin += window_base(L, p.window);
+    const bool real = begin + 32 * wave <= rmax;
+    load_k(tb, wave, real);
+    load_v(tb, wave, real);
+  }
   const int end = min(begin + p.chunk, L);
   if (end <= begin) {
     if (p.S == 1) {           // empty sequence: zero output rows
@@ -223,7 +232,7 @@ void decode_mfma_kernel(DecodeParams p) {
   // one tile: logits, online softmax, weighted sum; refills the tile's registers with tile tn
   auto process = [&](Tile& tl, int t, int tn) {
     const int p0 = begin + 32 * t;
-    const bool tail = p0 + 32 > end;
+    const bool tail = p0 + 32 > end || p0 < lo;
     const bool more = tn < ntiles;
 
     // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
@@ -247,18 +256,22 @@ void decode_mfma_kernel(DecodeParams p) {
     load_k(tl, tn, more);       // K registers are free: fetch the tile that will use them next
     if (t == wave) MQA_STAMP(3);
 
-    if (tail) {                 // ragged end of the range: drop positions >= end
+    if (tail) {                 // ragged end of the range / start of a window: drop positions outside [lo, end)
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (p0 + 16 * u + 4 * r + g >= end) {
+        for (int r = 0; r < 4; ++r) {
+          const int pos = p0 + 16 * u + 4 * r + g;
+          if (pos >= end || pos < lo) {
 #pragma unroll
             for (int hb = 0; hb < HB; ++hb) sc[u][hb][r] = -INFINITY;
           }
+        }
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (p0 + 4 * e + g >= end) tl.vr[e] = u32x4{0u, 0u, 0u, 0u};
+      for (int e = 0; e < 8; ++e) {
+        const int pos = p0 + 4 * e + g;
+        if (pos >= end || pos < lo) tl.vr[e] = u32x4{0u, 0u, 0u, 0u};
+      }
     }
 
     // ---- online softmax per head block; weights packed as MFMA B operands

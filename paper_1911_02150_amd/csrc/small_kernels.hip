@@ -38,7 +38,7 @@ void combine_kernel(DecodeParams p) {
     }
     int L = p.lens[seq / p.lens_div];
     L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-    const int nvalid = min(p.S, (L + p.chunk - 1) / p.chunk);
+    const int nvalid = min(p.S, (L - window_base(L, p.window) + p.chunk - 1) / p.chunk);
     if (nvalid > 0) {
       float M = -INFINITY;
 #pragma unroll
@@ -58,7 +58,7 @@ void combine_kernel(DecodeParams p) {
   } else {
     int L = p.lens[seq / p.lens_div];
     L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-    const int nvalid = min(p.S, (L + p.chunk - 1) / p.chunk);
+    const int nvalid = min(p.S, (L - window_base(L, p.window) + p.chunk - 1) / p.chunk);
     if (nvalid > 0) {
       float M = -INFINITY;
       for (int s = 0; s < nvalid; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.G]);

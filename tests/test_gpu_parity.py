@@ -397,3 +397,39 @@ def test_decode_step_in_a_hip_graph(m):
         assert torch.equal(o, expect[i]), f"replay {i} differs from the eager step"
         _ = (q * 2).sum().item()                         # unrelated eager work between replays
     assert torch.equal(lens, lens0 + 3)
+
+
+# ----------------------------------------------------------------- local attention (Section 4.1 variant)
+@pytest.mark.parametrize("window", [1, 31, 32, 33, 100, 5000])
+def test_mqa_decode_window_bf16(m, window):
+    lens = [1, 2, 31, 32, 33, 64, 65, 97, 300, 301, 0, 255]
+    c = mi.random_case(60, len(lens), 8, 301, 128, 128, cache="bf16", lens=lens)
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    dl = torch.from_numpy(c["lens"]).to(DEV)
+    o = m.mqa_decode_step_window(q, K, V, dl, window)
+    ref = orc.mqa_decode(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"], window=window)
+    check(o, ref, "bf16", f"window {window}")
+    if window >= 301:
+        assert torch.equal(o, m.mqa_decode_step(q, K, V, dl))
+
+
+def test_decode_window_other_paths(m):
+    # long window over a long cache: the ranges are split and merged (few sequences, many CUs)
+    c = mi.random_case(61, 2, 32, 3000, 128, 128, cache="bf16", lens=[3000, 1777])
+    q = torch.from_numpy(c["q"]).to(DEV)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    dl = torch.from_numpy(c["lens"]).to(DEV)
+    for window in (1024, 1500):
+        o = m.mqa_decode_step_window(q, K, V, dl, window)
+        ref = orc.mqa_decode(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"], window=window)
+        check(o, ref, "bf16", f"long window {window}")
+    # float32 cache (generic kernel) and the multi-head layout
+    c = mi.random_case(62, 3, 5, 130, 64, 32, cache="f32", lens=[130, 40, 7])
+    o = m.mqa_decode_step_window(torch.from_numpy(c["q"]).to(DEV), to_dev_cache(c["K"]), to_dev_cache(c["V"]),
+                                 torch.from_numpy(c["lens"]).to(DEV), 32)
+    check(o, orc.mqa_decode(c["q"], c["K"].astype(np.float64), c["V"].astype(np.float64), c["lens"], window=32), "f32", "generic window")
+    c = mi.random_case(63, 2, 3, 90, 128, 128, cache="bf16", lens=[90, 33], multi_head=True)
+    o = m.mha_decode_step_window(torch.from_numpy(c["q"]).to(DEV), to_dev_cache(c["K"]), to_dev_cache(c["V"]),
+                                 torch.from_numpy(c["lens"]).to(DEV), 32)
+    check(o, orc.mha_decode(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"], window=32), "bf16", "mha window")

@@ -327,3 +327,23 @@ def test_append_semantics():
     orc.append_kv(Kh, Vh, np.arange(4.0).reshape(1, 2, 2), np.arange(6.0).reshape(1, 2, 3), lh, cache="f64")
     assert np.array_equal(Kh[0, :, 1], [[0, 1], [2, 3]]) and np.array_equal(Vh[0, 1, 1], [3, 4, 5]) and lh[0] == 2
     assert np.all(Kh[0, :, [0, 2]] == 0)
+
+
+# ---------------------------------------------------------------- local window (Section 4.1)
+def test_window_is_a_shortened_cache():
+    g = _rng(30)
+    b, h, m, k, v = 3, 4, 40, 6, 5
+    q, K, V = g.normal(size=(b, h, k)), g.normal(size=(b, m, k)), g.normal(size=(b, m, v))
+    lens = [40, 13, 3]
+    for W in (1, 5, 32, 100):
+        got = orc.mqa_decode(q, K, V, lens, window=W)
+        for i, L in enumerate(lens):
+            lo = max(0, L - W)
+            ref = orc.mqa_decode(q[i:i + 1], K[i:i + 1, lo:L], V[i:i + 1, lo:L], [L - lo])    # the pinned full form
+            assert np.max(np.abs(got[i] - ref[0])) <= 1e-15
+        assert np.max(np.abs(got - np.array(bf.mqa_decode_bf(q.tolist(), K.tolist(), V.tolist(), lens, 1.0, W)))) <= 1e-14
+    # a window of one position returns the newest V row; a window longer than the cache changes nothing
+    assert np.array_equal(orc.mqa_decode(q, K, V, lens, window=1)[1], np.repeat(V[1, 12:13], h, 0))
+    assert np.array_equal(orc.mqa_decode(q, K, V, lens, window=64), orc.mqa_decode(q, K, V, lens))
+    Kh, Vh = np.repeat(K[:, None], h, 1), np.repeat(V[:, None], h, 1)
+    assert np.max(np.abs(orc.mha_decode(q, Kh, Vh, lens, window=5) - orc.mqa_decode(q, K, V, lens, window=5))) <= 1e-15
