@@ -130,6 +130,24 @@ int mha_decode_step_window(const float* q, const void* K, const void* V, const i
                            int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, int window,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * A whole prompt at once: the multi-query attention of the paper's Section 3 batched listing
+ * (`MultiqueryAttentionBatched`) with the causal mask of Section 2.3, fused (logits and weights
+ * never reach memory), for n consecutive queries per sequence against the cache.
+ *   mqa_append_kv_rows: as mqa_append_kv for n rows per sequence, k_new [b,n,h_kv,k],
+ *     v_new [b,n,h_kv,v]; lens[i] += n; a sequence without room for all n rows is left untouched.
+ *   mqa_prefill_attention: q [b,n,h,k] (the q projection of the n inputs, rows in that order),
+ *     o [b,n,h,v].  Call after the append: query j of sequence i sits at position
+ *     lens[i]-n+j and attends to positions 0..lens[i]-n+j.  lens[i] >= n is required (a query
+ *     with nothing to attend to yields zeros).  bf16 cache with k = v = 128 only
+ *     (MQA_ERR_SHAPE otherwise).  The n*h rows of a sequence share each K/V tile they read.
+ */
+int mqa_append_kv_rows(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
+                       int b, int n, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream);
+int mqa_prefill_attention(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                          int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same as mqa_decode_step / mha_decode_step with explicit launch tuning (NULL = defaults). */
 int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                        int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,

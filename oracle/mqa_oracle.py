@@ -227,6 +227,24 @@ def mqa_decode(q, K, V, lens, scale=1.0, window=None):
     return o
 
 
+def mqa_prefill(q, K, V, lens, scale=1.0):
+    """Attention of the Section 3 batched listing (`MultiqueryAttentionBatched`) for n consecutive
+    queries per sequence against a cache that already holds their rows, with the causal mask of
+    Section 2.3: q [b,n,h,k]; query j of sequence i sits at position lens[i]-n+j and attends to
+    positions 0..lens[i]-n+j.  Returns o [b,n,h,v]."""
+    q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
+    b, n, h, _ = q.shape
+    o = np.zeros((b, n, h, V.shape[-1]), dtype=F64)
+    for i in range(b):
+        L = int(lens[i])
+        pos = L - n + np.arange(n)                                   # positions of the n queries
+        logits = scale * np.einsum("nhk,mk->hnm", q[i], K[i, :L], optimize=True)
+        mask = np.where(np.arange(L)[None, :] <= pos[:, None], 0.0, -np.inf)      # [n, L]
+        weights = softmax64(logits + mask[None])
+        o[i] = np.einsum("hnm,mv->nhv", weights, V[i, :L], optimize=True)
+    return o
+
+
 def mha_decode(q, K, V, lens, scale=1.0, window=None):
     """Attention part of `MultiheadSelfAttentionIncremental` (Section 2.4):
     logits = einsum('bhk,bhmk->bhm'), softmax, o = einsum('bhm,bhmv->bhv').

@@ -17,7 +17,7 @@ MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
 
 EXPORTS = [
     "mqa_project_qkvo", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
-    "mqa_decode_step_window", "mha_decode_step_window", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
+    "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
@@ -56,6 +56,8 @@ def load_library(path: str = LIB_PATH):
     win = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.mqa_decode_step_window.argtypes = win
     lib.mha_decode_step_window.argtypes = win
+    lib.mqa_append_kv_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+    lib.mqa_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
     lib.mqa_decode_step_ex.argtypes = dec + [tp]
     lib.mha_decode_step_ex.argtypes = dec + [tp]
     lib.mqa_decode_partials.argtypes = dec + [tp]
@@ -228,6 +230,42 @@ def mqa_append_kv(K, V, k_new, v_new, lens, stream=None):
                            _cache_dtype(K), _stream(stream))
     if rc != 0:
         raise MqaError("mqa_append_kv", rc)
+
+
+def mqa_append_kv_rows(K, V, k_new, v_new, lens, stream=None):
+    """Appends n rows per sequence: k_new [b,n,k] / v_new [b,n,v] (multi-query) or [b,n,h,k] / [b,n,h,v]."""
+    lib = load_library()
+    for t, nm in ((K, "K"), (V, "V"), (k_new, "k_new"), (v_new, "v_new"), (lens, "lens")):
+        _check(t, nm)
+    b, n = k_new.shape[0], k_new.shape[1]
+    h_kv = K.shape[1] if K.dim() == 4 else 1
+    cap, k, v = K.shape[-2], K.shape[-1], V.shape[-1]
+    if k_new.numel() != b * n * h_kv * k or v_new.numel() != b * n * h_kv * v or K.shape[0] != b or lens.numel() != b:
+        raise ValueError("shape mismatch in mqa_append_kv_rows")
+    rc = lib.mqa_append_kv_rows(_ptr(K), _ptr(V), _ptr(k_new), _ptr(v_new), _ptr(lens), b, n, h_kv, cap, k, v,
+                                _cache_dtype(K), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_append_kv_rows", rc)
+
+
+def mqa_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=None):
+    """q [b,n,h,k], K [b,cap,k], V [b,cap,v] bf16, lens [b] (after the append) -> o [b,n,h,v]."""
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
+    b, n, h, k = q.shape
+    cap, v = V.shape[-2], V.shape[-1]
+    if tuple(K.shape) != (b, cap, k) or tuple(V.shape) != (b, cap, v) or lens.numel() != b:
+        raise ValueError("shape mismatch in mqa_prefill_attention")
+    if o is None:
+        o = torch.empty((b, n, h, v), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _default_workspace(q.device, mqa_decode_workspace_bytes(b, n * h, cap, v))
+    rc = lib.mqa_prefill_attention(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, n, h, cap, k, v,
+                                   _cache_dtype(K), float(scale), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_prefill_attention", rc)
+    return o
 
 
 def mqa_project_qkvo(mode, x, P, out=None, stream=None):

@@ -78,8 +78,13 @@ int check_decode_args(const float* q, const void* K, const void* V, const int32_
 int decode_impl(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                 int b, int h, int cap, int k, int v, int dt, float scale,
                 void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning,
-                bool multi_head, int phase, int window = 0) {
-  if (window < 0) return MQA_ERR_SHAPE;
+                bool multi_head, int phase, int window = 0, int causal_n = 0) {
+  if (window < 0 || causal_n < 0) return MQA_ERR_SHAPE;
+  const int h_true = h;
+  if (causal_n > 0) {          // n queries x h heads per sequence are n*h rows sharing the sequence's K/V
+    if (multi_head || (long long)h * causal_n > (1 << 20)) return MQA_ERR_SHAPE;
+    h = h * causal_n;
+  }
   int rc = check_decode_args(q, K, V, lens, o, b, h, cap, k, v, dt, (phase & 1) != 0);
   if (rc) return rc;
   Tuning tn;
@@ -91,8 +96,10 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   const int nseq = multi_head ? b * h : b;
   const int G = multi_head ? 1 : h;
   Plan pl;
+  if (causal_n > 0) tn.splits = 1;     // rows end at different positions: one range per workgroup, no merge pass
   rc = plan_decode(nseq, G, cap, window, k, v, dt == MQA_BF16, tn, &pl);
   if (rc) return rc;
+  if (causal_n > 0 && !pl.use_mfma) return MQA_ERR_SHAPE;       // causal rows: MFMA kernel only
   if (pl.S > 1) {
     if (!workspace || workspace_bytes < partial_bytes(nseq, pl.S, G, v)) return MQA_ERR_WORKSPACE;
     if (misaligned(workspace)) return MQA_ERR_ALIGN;
@@ -103,7 +110,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   p.part_m = p.part_o ? p.part_o + (size_t)nseq * pl.S * G * v : nullptr;
   p.part_l = p.part_m ? p.part_m + (size_t)nseq * pl.S * G : nullptr;
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
-  p.k = k; p.v = v; p.window = window; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
+  p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? h_true : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
 #ifdef MQA_TIMELINE
   p.timeline = g_timeline;
@@ -214,10 +221,32 @@ int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int3
   if ((k & 7) || (v & 7)) return MQA_ERR_SHAPE;
   if (misaligned(K) || misaligned(V) || misaligned(k_new) || misaligned(v_new) || misaligned(lens))
     return MQA_ERR_ALIGN;
-  if (launch_append(K, V, k_new, v_new, lens, b, h_kv, cap, k, v, dt == MQA_BF16,
+  if (launch_append(K, V, k_new, v_new, lens, b, h_kv, cap, k, v, 1, dt == MQA_BF16,
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return MQA_ERR_LAUNCH;
   return MQA_OK;
+}
+
+int mqa_append_kv_rows(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
+                       int b, int n, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream) {
+  if (!K || !V || !k_new || !v_new || !lens) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || n <= 0 || h_kv <= 0 || cap <= 0 || k <= 0 || v <= 0 || n > cap) return MQA_ERR_SHAPE;
+  if ((k & 7) || (v & 7)) return MQA_ERR_SHAPE;
+  if (misaligned(K) || misaligned(V) || misaligned(k_new) || misaligned(v_new) || misaligned(lens))
+    return MQA_ERR_ALIGN;
+  if (launch_append(K, V, k_new, v_new, lens, b, h_kv, cap, k, v, n, dt == MQA_BF16,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
+int mqa_prefill_attention(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                          int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (n <= 0 || n > cap) return MQA_ERR_SHAPE;
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, false, 3, 0, n);
 }
 
 int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,

@@ -25,6 +25,8 @@ struct DecodeParams {
   int nseq, G, cap, lens_div;
   int k, v;
   int window;            // > 0: attend only to the last `window` valid positions (0 = all)
+  int causal_h;          // > 0 (MFMA kernel): the G rows of a group are n = G/causal_h consecutive queries
+                         // x causal_h heads; query j sits at position L-n+j and sees positions <= its own
   int chunk;             // positions per range (multiple of 32)
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
@@ -52,7 +54,7 @@ hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t
 // small_kernels.hip
 hipError_t launch_combine(const DecodeParams& p, hipStream_t st);
 hipError_t launch_append(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
-                         int b, int h_kv, int cap, int k, int v, int is_bf16, hipStream_t st);
+                         int b, int h_kv, int cap, int k, int v, int n, int is_bf16, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t st);
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 

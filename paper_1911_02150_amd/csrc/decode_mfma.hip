@@ -184,7 +184,23 @@ void decode_mfma_kernel(DecodeParams p) {
     load_k(tb, wave, real);
     load_v(tb, wave, real);
   }
-  const int end = min(begin + p.chunk, L);
+  // Causal rows (prefill of n queries per sequence): row r = query r / h, at position L - n + r / h,
+  // attends to positions <= its own.  `end` is the largest such limit in this workgroup.
+  const int causal_h = p.causal_h;
+  const int nq = causal_h > 0 ? p.G / causal_h : 1;
+  int lim[HB];                                   // first position the lane's row (per head block) must NOT see
+  int lim_min = L, lim_max = L;
+  if (causal_h > 0) {
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) lim[hb] = max(0, L - nq + min(head0 + 16 * hb + i16, p.G - 1) / causal_h + 1);
+    lim_min = max(0, L - nq + head0 / causal_h + 1);
+    lim_max = max(0, L - nq + (min(head0 + NH, p.G) - 1) / causal_h + 1);
+  } else {
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) lim[hb] = L;
+  }
+  const int end = min(begin + p.chunk, lim_max);
+  const int mask_from = min(end, lim_min);        // tiles reaching beyond this position need masking
   if (end <= begin) {
     if (p.S == 1) {           // empty sequence: zero output rows
       for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
@@ -232,7 +248,7 @@ void decode_mfma_kernel(DecodeParams p) {
   // one tile: logits, online softmax, weighted sum; refills the tile's registers with tile tn
   auto process = [&](Tile& tl, int t, int tn) {
     const int p0 = begin + 32 * t;
-    const bool tail = p0 + 32 > end || p0 < lo;
+    const bool tail = p0 + 32 > mask_from || p0 < lo;
     const bool more = tn < ntiles;
 
     // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
@@ -262,10 +278,9 @@ void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int pos = p0 + 16 * u + 4 * r + g;
-          if (pos >= end || pos < lo) {
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb) sc[u][hb][r] = -INFINITY;
-          }
+          for (int hb = 0; hb < HB; ++hb)
+            if (pos >= min(end, lim[hb]) || pos < lo) sc[u][hb][r] = -INFINITY;
         }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -283,8 +298,11 @@ void decode_mfma_kernel(DecodeParams p) {
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float mnew = fmaxf(m_run[hb], mx);
+      // a causal row may have seen nothing yet (maximum still -inf): subtract 0 instead, so that
+      // its weights come out as 2^(-inf) = 0 rather than 2^(-inf + inf)
+      const float mref = mnew == -INFINITY ? 0.f : mnew;
       if (__any(mnew > m_run[hb])) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - mnew);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - mref);
         l_run[hb] *= alpha;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[hb][j] *= alpha;
@@ -296,7 +314,7 @@ void decode_mfma_kernel(DecodeParams p) {
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          pe[4 * u + r] = __builtin_amdgcn_exp2f(sc[u][hb][r] - m_run[hb]);
+          pe[4 * u + r] = __builtin_amdgcn_exp2f(sc[u][hb][r] - mref);
           sum += pe[4 * u + r];
         }
       l_run[hb] += sum;
@@ -386,14 +404,14 @@ void decode_mfma_kernel(DecodeParams p) {
     float lsum = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      const float f = __builtin_amdgcn_exp2f(fw[it][w] - M);   // wave 0 always has a tile: M finite
+      const float f = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(fw[it][w] - M);   // (a row that saw nothing)
       const float4 x = xw[it][w];
       a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
       lsum += f * lw[it][w];
     }
     const int head = head0 + hl;
     if (p.S == 1) {
-      const float inv = 1.0f / lsum;
+      const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;      // (a causal row with nothing to see: zeros)
       a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
       reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * kD)[c4] = a;
     } else {

@@ -85,23 +85,27 @@ template <typename T> __device__ __forceinline__ T to_cache(float x);
 template <> __device__ __forceinline__ float to_cache<float>(float x) { return x; }
 template <> __device__ __forceinline__ uint16_t to_cache<uint16_t>(float x) { return (uint16_t)float_to_bf16_rne(x); }
 
+// n rows per sequence at once (n = 1: one decode step; n > 1: a prompt).  New rows are
+// k_new [b, n, h_kv, k]; a sequence that cannot hold all n rows is left untouched.
 template <typename T>
 __global__ __launch_bounds__(256)
 void append_kernel(T* K, T* V, const float* k_new, const float* v_new, int32_t* lens,
-                   int h_kv, int cap, int k, int v) {
+                   int h_kv, int cap, int k, int v, int n) {
   const int i = blockIdx.x;
   const int L = lens[i];
   __syncthreads();
-  if (L < 0 || L >= cap) return;
-  for (int idx = threadIdx.x; idx < h_kv * k; idx += 256) {
-    const int j = idx / k, c = idx - j * k;
-    K[(((size_t)i * h_kv + j) * cap + L) * k + c] = to_cache<T>(k_new[(size_t)i * h_kv * k + idx]);
+  if (L < 0 || L + n > cap) return;
+  for (int idx = threadIdx.x; idx < n * h_kv * k; idx += 256) {
+    const int r = idx / (h_kv * k), rem = idx - r * (h_kv * k);
+    const int j = rem / k, c = rem - j * k;
+    K[(((size_t)i * h_kv + j) * cap + L + r) * k + c] = to_cache<T>(k_new[(size_t)i * n * h_kv * k + idx]);
   }
-  for (int idx = threadIdx.x; idx < h_kv * v; idx += 256) {
-    const int j = idx / v, c = idx - j * v;
-    V[(((size_t)i * h_kv + j) * cap + L) * v + c] = to_cache<T>(v_new[(size_t)i * h_kv * v + idx]);
+  for (int idx = threadIdx.x; idx < n * h_kv * v; idx += 256) {
+    const int r = idx / (h_kv * v), rem = idx - r * (h_kv * v);
+    const int j = rem / v, c = rem - j * v;
+    V[(((size_t)i * h_kv + j) * cap + L + r) * v + c] = to_cache<T>(v_new[(size_t)i * n * h_kv * v + idx]);
   }
-  if (threadIdx.x == 0) lens[i] = L + 1;
+  if (threadIdx.x == 0) lens[i] = L + n;
 }
 
 // Plain streaming read: every 16-byte word is loaded once, folded into a
@@ -140,13 +144,13 @@ hipError_t launch_combine(const DecodeParams& p, hipStream_t st) {
 }
 
 hipError_t launch_append(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
-                         int b, int h_kv, int cap, int k, int v, int is_bf16, hipStream_t st) {
+                         int b, int h_kv, int cap, int k, int v, int n, int is_bf16, hipStream_t st) {
   if (is_bf16)
     hipLaunchKernelGGL(append_kernel<uint16_t>, dim3(b), dim3(256), 0, st, (uint16_t*)K, (uint16_t*)V,
-                       k_new, v_new, lens, h_kv, cap, k, v);
+                       k_new, v_new, lens, h_kv, cap, k, v, n);
   else
     hipLaunchKernelGGL(append_kernel<float>, dim3(b), dim3(256), 0, st, (float*)K, (float*)V,
-                       k_new, v_new, lens, h_kv, cap, k, v);
+                       k_new, v_new, lens, h_kv, cap, k, v, n);
   return hipGetLastError();
 }
 

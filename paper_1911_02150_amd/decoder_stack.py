@@ -73,5 +73,28 @@ class DecoderStack:
             B.mqa_stack_add(x, self.feed_forward(l, x))
         return self.logits(x)
 
+    # -- a whole prompt at once (multi-query only): bulk append + fused causal attention per layer
+    def prefill(self, prompts: torch.Tensor) -> torch.Tensor:
+        """prompts [b,n] int32, caches empty.  Returns the logits of the last prompt position [b,vocab]."""
+        if self.multi_head:
+            raise NotImplementedError("prefill is built for the multi-query cache")
+        b, n = prompts.shape
+        positions = torch.arange(n, dtype=torch.int32, device=self.dev).repeat(b)
+        x = B.mqa_stack_embed(prompts.reshape(-1).to(torch.int32).contiguous(), positions, self.E, self.pos)   # [b*n,d]
+        for l, w in enumerate(self.layers):
+            hx = B.mqa_stack_layernorm(x)
+            q = B.mqa_project_qkvo(B.MQA_PROJ_Q, hx, w["P_q"]).view(b, n, self.h, self.k)
+            kn = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["P_k"]).view(b, n, self.k)
+            vn = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["P_v"]).view(b, n, self.v)
+            B.mqa_append_kv_rows(self.K[l], self.V[l], kn, vn, self.lens[l])
+            o = B.mqa_prefill_attention(q, self.K[l], self.V[l], self.lens[l])
+            B.mqa_stack_add(x, B.mqa_project_qkvo(B.MQA_PROJ_O, o.view(b * n, self.h, self.v), w["P_o"]))
+            hx = B.mqa_stack_layernorm(x)
+            u = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["W1"])
+            B.mqa_stack_relu(u)
+            B.mqa_stack_add(x, B.mqa_project_qkvo(B.MQA_PROJ_KV, u, w["W2"]))
+        last = x.view(b, n, self.d)[:, n - 1].contiguous()
+        return self.logits(last)
+
     def greedy(self, logits: torch.Tensor) -> torch.Tensor:
         return B.mqa_stack_argmax(logits)

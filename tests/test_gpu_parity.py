@@ -433,3 +433,70 @@ def test_decode_window_other_paths(m):
     o = m.mha_decode_step_window(torch.from_numpy(c["q"]).to(DEV), to_dev_cache(c["K"]), to_dev_cache(c["V"]),
                                  torch.from_numpy(c["lens"]).to(DEV), 32)
     check(o, orc.mha_decode(c["q"], mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"], window=32), "bf16", "mha window")
+
+
+# ----------------------------------------------------------------- prompt attention (causal, many queries at once)
+@pytest.mark.parametrize("b,n,h,prefix", [(2, 5, 8, 0), (3, 33, 8, 17), (2, 128, 8, 0), (1, 64, 3, 100), (2, 40, 32, 9)])
+def test_prefill_attention(m, b, n, h, prefix):
+    cap = prefix + n + 7
+    g = mi.rng(4000 + n, b)
+    q = g.standard_normal((b, n, h, 128), dtype=np.float32) / np.float32(np.sqrt(128)) * np.float32(3)
+    c = mi.random_case(70 + n, b, 1, cap, 128, 128, cache="bf16", lens=[prefix + n] * b)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.from_numpy(c["lens"]).to(DEV)
+    o = m.mqa_prefill_attention(torch.from_numpy(q).to(DEV), K, V, lens)
+    ref = orc.mqa_prefill(q, mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"])
+    check(o, ref, "bf16", f"prefill b={b} n={n} h={h} prefix={prefix}")
+    # the same rows through n single-token decode steps
+    j = n // 2
+    step = m.mqa_decode_step(torch.from_numpy(np.ascontiguousarray(q[:, j])).to(DEV), K, V,
+                             torch.full((b,), prefix + j + 1, dtype=torch.int32, device=DEV))
+    assert float((step - o[:, j]).abs().max()) <= 1e-4
+
+
+def test_prefill_prompt_then_decode(m):
+    """A prompt written with one bulk append and attended in one call, then a decode step on top:
+    the cache and lengths the prefill leaves are what the incremental path continues from."""
+    b, n, h, d, cap = 4, 48, 8, 256, 64
+    g = mi.rng(4100, 0)
+    X = g.standard_normal((b, n + 1, d), dtype=np.float32)
+    P_q = g.standard_normal((h, d, 128), dtype=np.float32) / np.float32(np.sqrt(d))
+    P_k = g.standard_normal((d, 128), dtype=np.float32) / np.float32(np.sqrt(d))
+    P_v = g.standard_normal((d, 128), dtype=np.float32) / np.float32(np.sqrt(d))
+    dX = torch.from_numpy(X).to(DEV)
+    dPq, dPk, dPv = (torch.from_numpy(a).to(DEV) for a in (P_q, P_k, P_v))
+    K = torch.full((b, cap, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    V = torch.full((b, cap, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lens = torch.zeros(b, dtype=torch.int32, device=DEV)
+    rows = dX[:, :n].reshape(b * n, d).contiguous()
+    q = m.mqa_project_qkvo(m.MQA_PROJ_Q, rows, dPq).view(b, n, h, 128)
+    kn = m.mqa_project_qkvo(m.MQA_PROJ_KV, rows, dPk).view(b, n, 128)
+    vn = m.mqa_project_qkvo(m.MQA_PROJ_KV, rows, dPv).view(b, n, 128)
+    m.mqa_append_kv_rows(K, V, kn, vn, lens)
+    assert np.array_equal(lens.cpu().numpy(), np.full(b, n))
+    assert torch.equal(K[:, :n], kn.to(torch.bfloat16)) and torch.isnan(K[:, n:].float()).all()
+    o = m.mqa_prefill_attention(q, K, V, lens)
+    # oracle on the GPU's own rounded cache rows would be an input from the HIP path: use the oracle's rows instead
+    Kr, Vr = np.zeros((b, cap, 128)), np.zeros((b, cap, 128))
+    lr = np.zeros(b, dtype=np.int64)
+    for t in range(n):
+        orc.append_kv(Kr, Vr, orc.project_kv(X[:, t], P_k), orc.project_kv(X[:, t], P_v), lr, cache="bf16")
+    K[:, :n].copy_(torch.from_numpy(Kr[:, :n]).to(torch.bfloat16))      # oracle -> GPU, near-ties aside the same rows
+    V[:, :n].copy_(torch.from_numpy(Vr[:, :n]).to(torch.bfloat16))
+    o = m.mqa_prefill_attention(q, K, V, lens)
+    Q = np.einsum("bnd,hdk->bnhk", X[:, :n].astype(np.float64), P_q.astype(np.float64))
+    check(o, orc.mqa_prefill(Q, Kr, Vr, lr), "bf16", "prefill after bulk append")
+    # one more token through the incremental path
+    x = dX[:, n].contiguous()
+    m.mqa_append_kv(K, V, m.mqa_project_qkvo(m.MQA_PROJ_KV, x, dPk), m.mqa_project_qkvo(m.MQA_PROJ_KV, x, dPv), lens)
+    o1 = m.mqa_decode_step(m.mqa_project_qkvo(m.MQA_PROJ_Q, x, dPq), K, V, lens)
+    orc.append_kv(Kr, Vr, orc.project_kv(X[:, n], P_k), orc.project_kv(X[:, n], P_v), lr, cache="bf16")
+    K[:, n].copy_(torch.from_numpy(Kr[:, n]).to(torch.bfloat16))
+    V[:, n].copy_(torch.from_numpy(Vr[:, n]).to(torch.bfloat16))
+    o1 = m.mqa_decode_step(m.mqa_project_qkvo(m.MQA_PROJ_Q, x, dPq), K, V, lens)
+    check(o1, orc.mqa_decode(orc.project_q(X[:, n], P_q), Kr, Vr, lr), "bf16", "decode after prefill")
+    # a sequence without room for the whole prompt is left untouched
+    lens2 = torch.tensor([cap - 3, 0, 0, 0], dtype=torch.int32, device=DEV)
+    K2 = torch.zeros_like(K)
+    m.mqa_append_kv_rows(K2, torch.zeros_like(V), kn, vn, lens2)
+    assert lens2.cpu().tolist() == [cap - 3, n, n, n] and float(K2[0].float().abs().max()) == 0.0

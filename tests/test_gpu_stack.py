@@ -137,3 +137,34 @@ def test_decoder_stack_teacher_forced(m, multi_head):
     print(f"decoder stack {'mha' if multi_head else 'mqa'}: worst y err {worst_y:.2e}, worst logit err {worst_logit:.2e} "
           f"(max |logit| ~{np.abs(logits_ref).max():.0f}), greedy agreement {agree}/{compared} "
           f"({near_ties} near-ties), near-tie rounding differences in the caches {flips}")
+
+
+def test_stack_prefill_matches_incremental_and_oracle(m):
+    """The prompt through one prefill call per layer == the prompt token by token (GPU vs GPU), and
+    both give the oracle's logits; decoding then continues from the caches the prefill left."""
+    from paper_1911_02150_amd.decoder_stack import DecoderStack
+    b, n, cap = 6, 45, 64
+    w = mi.config3_weights(layers=2, d=256, h=8, k=128, v=128, d_ff=512, vocab=1000, max_pos=cap)
+    prompts = mi.rng(3, 555).integers(0, 1000, size=(b, n))
+    dp = torch.from_numpy(prompts.astype(np.int32)).to(DEV)
+    a = DecoderStack(w, b, cap, False, DEV)
+    logits_pre = a.prefill(dp)
+    inc = DecoderStack(w, b, cap, False, DEV)
+    for t in range(n):
+        logits_inc = inc.step(dp[:, t].contiguous(), t)
+    ref = ods.OracleStack(w, b, cap, False, cache="bf16")
+    for t in range(n):
+        logits_ref = ref.step(prompts[:, t], t)
+    torch.cuda.synchronize()
+    scale = float(np.abs(logits_ref).max())
+    # the caches of the two GPU paths agree except at near-ties of the bf16 rounding (float32 sums in another order)
+    for l in range(2):
+        assert torch.equal(a.lens[l], inc.lens[l])
+        diff = (a.K[l].float() - inc.K[l].float()).abs()
+        assert float((diff > 0).float().mean()) < 2e-2 and float(diff.max()) <= 2.0 ** -4
+    assert float((logits_pre - logits_inc).abs().max()) <= 2e-3 * scale
+    assert np.max(np.abs(logits_pre.cpu().numpy() - logits_ref)) <= 2e-3 * scale
+    # one decode step on top of the prefilled caches
+    tok = ods.greedy_token(logits_ref)
+    nxt = a.step(torch.from_numpy(tok.astype(np.int32)).to(DEV), n)
+    assert np.max(np.abs(nxt.cpu().numpy() - ref.step(tok, n))) <= 2e-3 * scale

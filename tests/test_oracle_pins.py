@@ -347,3 +347,30 @@ def test_window_is_a_shortened_cache():
     assert np.array_equal(orc.mqa_decode(q, K, V, lens, window=64), orc.mqa_decode(q, K, V, lens))
     Kh, Vh = np.repeat(K[:, None], h, 1), np.repeat(V[:, None], h, 1)
     assert np.max(np.abs(orc.mha_decode(q, Kh, Vh, lens, window=5) - orc.mqa_decode(q, K, V, lens, window=5))) <= 1e-15
+
+
+# ---------------------------------------------------------------- prompt attention (causal, batched)
+def test_prefill_equals_stepwise_decode_and_batched_listing():
+    g = _rng(31)
+    b, n, h, k, v, d = 2, 7, 3, 4, 5, 6
+    prefix = [0, 4]                                  # positions already in the cache before the n new ones
+    cap = n + 4
+    K, V = g.normal(size=(b, cap, k)), g.normal(size=(b, cap, v))
+    q = g.normal(size=(b, n, h, k))
+    lens = [prefix[0] + n, prefix[1] + n]
+    got = orc.mqa_prefill(q, K, V, lens, scale=0.7)
+    for i in range(b):
+        for j in range(n):                           # one query at a time through the pinned decode step
+            ref = orc.mqa_decode(q[i:i + 1, j], K[i:i + 1], V[i:i + 1], [prefix[i] + j + 1], scale=0.7)
+            assert np.max(np.abs(got[i, j] - ref[0])) <= 1e-14
+    # whole layer: projections + prefill attention == the Section 3 batched listing with a causal mask
+    X = g.normal(size=(b, n, d))
+    P_q, P_o = g.normal(size=(h, d, k)), g.normal(size=(h, d, v))
+    P_k, P_v = g.normal(size=(d, k)), g.normal(size=(d, v))
+    Kc = np.einsum("bnd,dk->bnk", X, P_k)
+    Vc = np.einsum("bnd,dv->bnv", X, P_v)
+    Q = np.einsum("bnd,hdk->bnhk", X, P_q)
+    o = orc.mqa_prefill(Q, Kc, Vc, [n, n])
+    Y = np.einsum("bnhv,hdv->bnd", o, P_o)
+    ref = orc.multiquery_attention_batched(X, X, orc.causal_mask(b, h, n), P_q, P_k, P_v, P_o)
+    assert np.max(np.abs(Y - ref)) <= 1e-12
