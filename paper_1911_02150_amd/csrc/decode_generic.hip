@@ -139,9 +139,9 @@ hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t
   const size_t lds = ((size_t)kHeads * p.k + (size_t)kTile * (p.k + 1) + kHeads * kTile + 3 * kHeads) * sizeof(float);
   const dim3 grid((unsigned)((size_t)p.nseq * p.S)), block(kThreads);
   void (*kern)(DecodeParams) = is_bf16 ? decode_generic_kernel<uint16_t> : decode_generic_kernel<float>;
-  if (lds > 64 * 1024) {
+  if (lds > 64 * 1024) {     // opt in to more than 64 KiB of LDS (largest case: k = 256)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);

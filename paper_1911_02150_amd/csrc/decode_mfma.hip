@@ -446,14 +446,16 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
     default: kern = MQA_PICK(false, false); break;
   }
 #undef MQA_PICK
-  if (q_bytes + merge_bytes > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per kernel variant
-    static bool done[8] = {};
+  if (q_bytes + merge_bytes > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per device and kernel variant
+    static bool done[64][8] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
     const int slot = (flags & 3) | (ntl ? 4 : 0);
-    if (!done[slot]) {
+    if (!done[dev][slot]) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(q_bytes + merge_bytes));
       if (e != hipSuccess) return e;
-      done[slot] = true;
+      done[dev][slot] = true;
     }
   }
   hipLaunchKernelGGL(kern, grid, block, lds, st, p);
