@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-mha", action="store_true", help="do not time the 8 GiB multi-head twin")
     ap.add_argument("--skip-cpu-baseline", action="store_true", help="do not time the CPU oracle")
+    ap.add_argument("--skip-other-workloads", action="store_true", help="do not time workloads 1, 2, 3 and 5")
     ap.add_argument("--splits", type=int, default=0, help="override the number of position ranges")
     ap.add_argument("--flags", type=int, default=0, help="override kernel variant flags")
     return ap.parse_args()
@@ -74,6 +75,116 @@ def traffic_from_profile():
     except OSError:
         pass
     return None
+
+
+def graph_time_us(fn, replays=20, repeat=10):
+    """GPU time of the launches `fn(stream)` enqueues.  `repeat` copies of them are captured in one HIP
+    graph (so that neither the host's launch rate nor the ~10 us cost of launching a graph is measured)
+    and the graph is replayed `replays` times; returns microseconds per copy."""
+    import torch
+    fn(None)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(repeat):
+                fn(side)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(5):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * repeat) * 1e3
+
+
+def other_workloads(m, mi, dev):
+    """Latency of the other workloads' steps (synthetic tensors of their shapes; values do not matter
+    for timing, parity is in the tests).  Appends past capacity are no-ops, so replays are identical."""
+    import numpy as np
+    import torch
+    out = {}
+
+    def layer_step_fn(b, h, d, k, v, cap, length, mh, dtype):
+        x = torch.randn(b, d, device=dev)
+        Pq = torch.randn(h, d, k, device=dev) / d ** 0.5
+        Po = torch.randn(h, d, v, device=dev) / d ** 0.5
+        Pk = torch.randn((h, d, k) if mh else (d, k), device=dev) / d ** 0.5
+        Pv = torch.randn((h, d, v) if mh else (d, v), device=dev) / d ** 0.5
+        shp = (b, h, cap, k) if mh else (b, cap, k)
+        K = torch.randn(shp, device=dev).to(dtype)
+        V = torch.randn(shp, device=dev).to(dtype)
+        lens = torch.full((b,), length, dtype=torch.int32, device=dev)       # full: the append is a no-op
+        q = torch.empty(b, h, k, device=dev)
+        kn = torch.empty((b, h, k) if mh else (b, k), device=dev)
+        vn = torch.empty_like(kn)
+        o = torch.empty(b, h, v, device=dev)
+        y = torch.empty(b, d, device=dev)
+        ws = torch.empty(m.mqa_decode_workspace_bytes(b, h, cap, v), dtype=torch.uint8, device=dev)
+        kvm = m.MQA_PROJ_KV_MH if mh else m.MQA_PROJ_KV
+        dec = m.mha_decode_step if mh else m.mqa_decode_step
+
+        def fn(st):
+            m.mqa_project_qkvo(m.MQA_PROJ_Q, x, Pq, out=q, stream=st)
+            m.mqa_project_qkvo(kvm, x, Pk, out=kn, stream=st)
+            m.mqa_project_qkvo(kvm, x, Pv, out=vn, stream=st)
+            m.mqa_append_kv(K, V, kn, vn, lens, stream=st)
+            dec(q, K, V, lens, o=o, workspace=ws, stream=st)
+            m.mqa_project_qkvo(m.MQA_PROJ_O, o, Po, out=y, stream=st)
+
+        def attn(st):
+            dec(q, K, V, lens, o=o, workspace=ws, stream=st)
+        return fn, attn
+
+    # workload 1: one fp32 step, b=1, m=128 (projection of the 128-row memory excluded)
+    fn, attn = layer_step_fn(1, 8, 1024, 128, 128, 128, 128, False, torch.float32)
+    out["1_single_step_fp32"] = {"layer_step_us": graph_time_us(fn), "attention_us": graph_time_us(attn)}
+    # workload 2: b=128, cache of 128 positions, one layer: q/k/v projections, append, attention, output projection
+    for mh in (False, True):
+        fn, attn = layer_step_fn(128, 8, 1024, 128, 128, 128, 128, mh, torch.bfloat16)
+        t, ta = graph_time_us(fn), graph_time_us(attn)
+        out["2_incremental_b128_" + ("mha" if mh else "mqa")] = {
+            "layer_step_us": t, "attention_us": ta, "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
+    # workload 3: six such layers at 256 cached positions plus feed-forward, final layernorm, logits, argmax
+    for mh in (False, True):
+        from paper_1911_02150_amd.decoder_stack import DecoderStack
+        cfg = mi.CONFIGS[3]
+        w = mi.config3_weights(cfg["layers"], cfg["d"], cfg["h"], cfg["k"], cfg["v"], cfg["d_ff"], cfg["vocab"],
+                               cfg["cap"], mh)
+        st_ = DecoderStack(w, cfg["b"], cfg["cap"], mh, dev)
+        for l in range(cfg["layers"]):
+            st_.lens[l].fill_(cfg["cap"])
+        tok = torch.zeros(cfg["b"], dtype=torch.int32, device=dev)
+
+        def full(stream):
+            with torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream()):
+                st_.greedy(st_.step(tok, cfg["cap"] - 1))
+        t = graph_time_us(full, replays=10, repeat=3)
+        out["3_decoder_stack_" + ("mha" if mh else "mqa")] = {
+            "step_us": t, "us_per_token": t / cfg["b"], "tokens_per_s": cfg["b"] / (t * 1e-6),
+            "cached_positions": cfg["cap"], "layers": cfg["layers"]}
+        del st_, w
+    # workload 5: ragged batch, attention only
+    cfg = mi.CONFIGS[5]
+    b, h, cap = cfg["b"], cfg["h"], cfg["cap"]
+    lens_np = mi.rng(5, 8).integers(1, cap + 1, size=(b,)).astype(np.int32)
+    lens = torch.from_numpy(lens_np).to(dev)
+    q = torch.randn(b, h, 128, device=dev) / 128 ** 0.5
+    o = torch.empty(b, h, 128, device=dev)
+    Ks = [torch.randn(b, cap, 128, device=dev).to(torch.bfloat16) for _ in range(2)]
+    Vs = [torch.randn(b, cap, 128, device=dev).to(torch.bfloat16) for _ in range(2)]
+    ws = torch.empty(m.mqa_decode_workspace_bytes(b, h, cap, 128), dtype=torch.uint8, device=dev)
+    ms = time_region(lambda i: m.mqa_decode_step(q, Ks[i % 2], Vs[i % 2], lens, o=o, workspace=ws), 30, 5, settle_s=0.1)
+    kvb = int(lens_np.sum()) * 512
+    out["5_ragged_large_batch"] = {"step_us": ms * 1e3, "kv_bytes": kvb, "kv_GBps": kvb / (ms * 1e-3) / 1e9,
+                                   "frac_of_peak": kvb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    return out
 
 
 def cpu_baseline(q, K_bits, V_bits, budget_s=12.0):
@@ -186,6 +297,11 @@ def main():
                "data": "torch.randn on the device, seeded (timing only; parity uses the host-seeded blocks)"}
         del Kh, Vh
 
+    others = None
+    if not args.skip_other_workloads:
+        del Ks, Vs
+        others = other_workloads(m, mi, dev)
+
     cpu = None
     if not args.skip_cpu_baseline:
         cpu = cpu_baseline(q_np, K_np[:b], V_np[:b])
@@ -200,7 +316,7 @@ def main():
                    "kv_sets_rotated": nbuf, "position_ranges": splits},
         "step_us": step_us, "tokens_per_s": b / (ms_step * 1e-3), "frac_of_peak": value / HBM_PEAK_GBPS,
         "stream_read_GBps": stream_read_gbps, "stream_copy_GBps": stream_copy_gbps,
-        "roofline": roofline, "mha": mha, "cpu_baseline": cpu,
+        "roofline": roofline, "mha": mha, "other_workloads": others, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 
