@@ -31,7 +31,9 @@ Parity pins (tests/test_oracle_*.py): brute-force enumeration on tiny shapes,
 softmax against scipy, weights sum to one, MQA == MHA with shared K/V,
 incremental == causally masked batched attention, closed forms (one position,
 zero query, dominant logit, shift and permutation invariance, convex hull,
-a window as a shortened cache, a window of one position),
+a window as a shortened cache, a window of one position, beams as
+separate sequences with materialised memories, moving a row between the shared and the
+own part),
 torch float64 scaled-dot-product attention as an independent routine, split
 and recombine of the softmax state, NaN rows beyond the length, and bf16
 rounding against torch's cast.  No function here is "parity unpinned".
@@ -243,6 +245,47 @@ def mqa_prefill(q, K, V, lens, scale=1.0):
         weights = softmax64(logits + mask[None])
         o[i] = np.einsum("hnm,mv->nhv", weights, V[i, :L], optimize=True)
     return o
+
+
+def mqa_decode_beams(q, K_src, V_src, lens_src, K_beam, V_beam, lens_beam, scale=1.0):
+    """Beam search decoding (Section 4.1 decodes with beam 4; Table 2's last column) of the
+    Section 3 step when the `beam` hypotheses of a source share their first positions (the source
+    or prompt) and differ only in the positions each hypothesis produced itself.  The memory of
+    hypothesis (i, e) is, by definition, the rows K_src[i, :lens_src[i]] followed by
+    K_beam[i, e, :lens_beam[i, e]] (likewise V); the step is plain dot-product attention over it.
+    q [b,beam,h,k], K_src [b,cap_s,k], V_src [b,cap_s,v], K_beam [b,beam,cap_t,k],
+    V_beam [b,beam,cap_t,v], lens_beam [b,beam] -> o [b,beam,h,v]."""
+    q, K_src, V_src, K_beam, V_beam = (np.asarray(a, dtype=F64) for a in (q, K_src, V_src, K_beam, V_beam))
+    lens_beam = np.asarray(lens_beam).reshape(q.shape[0], q.shape[1])
+    b, beam, h, _ = q.shape
+    o = np.zeros((b, beam, h, V_src.shape[-1]), dtype=F64)
+    for i in range(b):
+        Ls = int(lens_src[i])
+        for e in range(beam):
+            Lt = int(lens_beam[i, e])
+            Kmem = np.concatenate([K_src[i, :Ls], K_beam[i, e, :Lt]], axis=0)
+            Vmem = np.concatenate([V_src[i, :Ls], V_beam[i, e, :Lt]], axis=0)
+            if Kmem.shape[0] == 0:
+                continue
+            for j in range(h):
+                o[i, e, j] = dot_product_attention(scale * q[i, e, j], Kmem, Vmem)
+    return o
+
+
+def beam_reorder_kv(K, V, lens, parent):
+    """Cache bookkeeping of beam search: after a step, hypothesis slot r continues hypothesis
+    parent[r] (slots are numbered over all sources, r = i*beam + e), so it takes over that
+    hypothesis' rows and length.  K [n,cap,k] (or [n,h,cap,k]), lens [n], parent [n] ->
+    (K', V', lens').  Rows at and beyond the length are never read; they are returned as zeros."""
+    K, V = np.asarray(K), np.asarray(V)
+    lens, parent = np.asarray(lens), np.asarray(parent)
+    K2, V2 = np.zeros_like(K), np.zeros_like(V)
+    lens2 = lens[parent].copy()
+    for r in range(K.shape[0]):
+        L = int(lens2[r])
+        K2[r, ..., :L, :] = K[parent[r], ..., :L, :]
+        V2[r, ..., :L, :] = V[parent[r], ..., :L, :]
+    return K2, V2, lens2
 
 
 def mha_decode(q, K, V, lens, scale=1.0, window=None):

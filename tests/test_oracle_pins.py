@@ -374,3 +374,89 @@ def test_prefill_equals_stepwise_decode_and_batched_listing():
     Y = np.einsum("bnhv,hdv->bnd", o, P_o)
     ref = orc.multiquery_attention_batched(X, X, orc.causal_mask(b, h, n), P_q, P_k, P_v, P_o)
     assert np.max(np.abs(Y - ref)) <= 1e-12
+
+
+# ---------------------------------------------------------------- beam search (Section 4.1, Table 2 last column)
+def _beam_case(seed, b=3, beam=4, h=2, cap_s=7, cap_t=5, k=3, v=4):
+    g = _rng(seed)
+    q = g.normal(size=(b, beam, h, k)) * 2
+    Ks, Vs = g.normal(size=(b, cap_s, k)), g.normal(size=(b, cap_s, v))
+    Kt, Vt = g.normal(size=(b, beam, cap_t, k)), g.normal(size=(b, beam, cap_t, v))
+    ls = g.integers(0, cap_s + 1, size=b)
+    lt = g.integers(0, cap_t + 1, size=(b, beam))
+    return q, Ks, Vs, ls, Kt, Vt, lt
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_beams_equal_separate_sequences_with_materialised_memories(seed):
+    """Every hypothesis as its own sequence whose memory holds a private copy of the shared rows
+    followed by its own: the multi-query step over those b*beam sequences (pinned above, and the
+    pure-Python enumeration) must give the same outputs."""
+    q, Ks, Vs, ls, Kt, Vt, lt = _beam_case(seed)
+    b, beam, h, k = q.shape
+    cap = Ks.shape[1] + Kt.shape[2]
+    K = np.full((b * beam, cap, k), np.nan)
+    V = np.full((b * beam, cap, Vs.shape[-1]), np.nan)
+    lens = np.zeros(b * beam, dtype=int)
+    for i in range(b):
+        for e in range(beam):
+            r = i * beam + e
+            K[r, :ls[i]], V[r, :ls[i]] = Ks[i, :ls[i]], Vs[i, :ls[i]]
+            K[r, ls[i]:ls[i] + lt[i, e]], V[r, ls[i]:ls[i] + lt[i, e]] = Kt[i, e, :lt[i, e]], Vt[i, e, :lt[i, e]]
+            lens[r] = ls[i] + lt[i, e]
+    got = orc.mqa_decode_beams(q, Ks, Vs, ls, Kt, Vt, lt, scale=0.7)
+    flat = orc.mqa_decode(q.reshape(b * beam, h, k), K, V, lens, scale=0.7)
+    assert np.max(np.abs(got.reshape(flat.shape) - flat)) <= 1e-14
+    enum = np.array(bf.mqa_decode_bf(q.reshape(b * beam, h, k).tolist(), np.nan_to_num(K).tolist(),
+                                     np.nan_to_num(V).tolist(), lens.tolist(), scale=0.7))
+    assert np.max(np.abs(got.reshape(enum.shape) - enum)) <= 1e-12
+
+
+def test_beams_special_cases():
+    q, Ks, Vs, ls, Kt, Vt, lt = _beam_case(11)
+    b, beam, h, k = q.shape
+    # no own positions: all hypotheses of a source are extra heads over the shared memory
+    zero = np.zeros_like(lt)
+    ls1 = np.maximum(ls, 1)
+    got = orc.mqa_decode_beams(q, Ks, Vs, ls1, Kt, Vt, zero)
+    ref = orc.mqa_decode(q.reshape(b, beam * h, k), Ks, Vs, ls1)
+    assert np.max(np.abs(got.reshape(ref.shape) - ref)) <= 1e-14
+    # no shared positions: b*beam independent sequences
+    got = orc.mqa_decode_beams(q, Ks, Vs, np.zeros_like(ls), Kt, Vt, lt)
+    ref = orc.mqa_decode(q.reshape(b * beam, h, k), Kt.reshape(b * beam, -1, k), Vt.reshape(b * beam, -1, Vt.shape[-1]),
+                         lt.reshape(-1))
+    assert np.max(np.abs(got.reshape(ref.shape) - ref)) <= 1e-14
+    # attention does not care which part a row sits in: move the last shared row of source 0 to
+    # the end of every hypothesis' own part
+    ls2, lt2 = ls.copy(), lt.copy()
+    ls2[0], lt2[0] = 3, 2
+    base = orc.mqa_decode_beams(q, Ks, Vs, ls2, Kt, Vt, lt2)
+    Kt3, Vt3, ls3, lt3 = Kt.copy(), Vt.copy(), ls2.copy(), lt2.copy()
+    Kt3[0, :, 2], Vt3[0, :, 2] = Ks[0, 2], Vs[0, 2]
+    ls3[0], lt3[0] = 2, 3
+    moved = orc.mqa_decode_beams(q, Ks, Vs, ls3, Kt3, Vt3, lt3)
+    assert np.max(np.abs(base - moved)) <= 1e-14
+    # nothing to attend to: zeros
+    assert not orc.mqa_decode_beams(q, Ks, Vs, np.zeros_like(ls), Kt, Vt, zero).any()
+
+
+def test_beam_reorder_semantics():
+    g = _rng(5)
+    n, cap, k = 8, 6, 3
+    K, V = g.normal(size=(n, cap, k)), g.normal(size=(n, cap, 2))
+    lens = np.array([0, 1, 6, 3, 2, 5, 4, 6])
+    parent = np.array([2, 2, 1, 0, 7, 7, 7, 3])      # slots may be dropped (4, 5, 6) or duplicated
+    K2, V2, lens2 = orc.beam_reorder_kv(K, V, lens, parent)
+    assert lens2.tolist() == [6, 6, 1, 0, 6, 6, 6, 3]
+    for r in range(n):
+        for t in range(lens2[r]):
+            assert K2[r, t].tolist() == K[parent[r], t].tolist() and V2[r, t].tolist() == V[parent[r], t].tolist()
+    # identity permutation keeps every valid row; a step after the reorder sees the parent's memory
+    K3, V3, lens3 = orc.beam_reorder_kv(K, V, lens, np.arange(n))
+    q = g.normal(size=(n, 2, k))
+    assert np.array_equal(orc.mqa_decode(q, K3, V3, lens3), orc.mqa_decode(q, K, V, lens))
+    assert np.array_equal(orc.mqa_decode(q, K2, V2, lens2)[4], orc.mqa_decode(q[4:5], K[7:8], V[7:8], lens[7:8])[0])
+    # multi-head caches [n, h, cap, k]
+    Kh = g.normal(size=(n, 2, cap, k))
+    Kh2, _, _ = orc.beam_reorder_kv(Kh, Kh, lens, parent)
+    assert np.array_equal(Kh2[0, :, :6], Kh[2, :, :6]) and np.array_equal(Kh2[7, 1, :3], Kh[3, 1, :3])
