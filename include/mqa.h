@@ -148,6 +148,36 @@ int mqa_prefill_attention(const float* q, const void* K, const void* V, const in
                           int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Beam search (the paper decodes with beam 4 in Section 4.1 and times it in Table 2): the
+ * `beam` hypotheses of a source share the memory rows they have in common (the source / prompt)
+ * and own only the rows they produced themselves.  The memory of hypothesis (i, e) is
+ * K_src[i, :lens_src[i]] followed by K_own[i, e, :lens_own[i*beam+e]] (likewise V); the step is
+ * the Section 3 attention over it.  The shared rows are read once per source for all beam*h
+ * query rows; the own rows once per hypothesis.
+ *   q [b,beam,h,k] device float32; K_src [b,cap_src,k], V_src [b,cap_src,v], lens_src [b];
+ *   K_own [b,beam,cap_own,k], V_own [b,beam,cap_own,v], lens_own [b*beam]; o [b,beam,h,v].
+ *   A hypothesis with no valid row in either part yields zeros.  Always uses the workspace:
+ *   at least mqa_decode_beams_workspace_bytes(...) bytes (0 = unsupported sizes), 16-byte aligned.
+ * mqa_beam_reorder_kv: after the search has chosen, for every hypothesis slot r (r = i*beam + e over
+ * all sources), the hypothesis parent[r] it continues, slot r of the destination cache receives
+ * rows [0, lens_src[parent[r]]) of slot parent[r] of the source cache and its length.  K_* are
+ * [n,h_kv,cap,k] (h_kv = 1 for multi-query), V_* [n,h_kv,cap,v], lens_* [n], parent [n] (values
+ * outside [0,n) are clamped).  Source and destination must be different buffers (MQA_ERR_SHAPE
+ * if a pointer pair is identical; partial overlap is undefined).  Destination rows at and beyond
+ * the new length are left as they were.  With multi-query caches this moves 1/h of the bytes
+ * the multi-head layout moves.
+ */
+int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, const int32_t* lens_src,
+                          const void* K_own, const void* V_own, const int32_t* lens_own, float* o,
+                          int b, int beam, int h, int cap_src, int cap_own, int k, int v, mqa_dtype dt,
+                          float scale, void* workspace, size_t workspace_bytes, void* stream);
+size_t mqa_decode_beams_workspace_bytes(int b, int beam, int h, int cap_src, int cap_own, int k, int v,
+                                        mqa_dtype dt);
+int mqa_beam_reorder_kv(const void* K_src, const void* V_src, const int32_t* lens_src, const int32_t* parent,
+                        void* K_dst, void* V_dst, int32_t* lens_dst,
+                        int n, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream);
+
 /* Same as mqa_decode_step / mha_decode_step with explicit launch tuning (NULL = defaults). */
 int mqa_decode_step_ex(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                        int b, int h, int cap, int k, int v, mqa_dtype dt, float scale,

@@ -248,6 +248,47 @@ def random_case(seed, b, h, cap, k, v, cache="bf16", lens="full", multi_head=Fal
     return dict(q=q, K=K, V=V, lens=L)
 
 
+def beam_case(seed, b, beam, h, cap_src, cap_own, k, v, cache="bf16", lens_src="ragged", lens_own="ragged",
+              poison=True):
+    """A seeded beam-search step: `beam` hypotheses per source share the source's rows and own the
+    rows they produced (the shape of the paper's beam-4 translation decoding: a source / prompt of
+    up to cap_src positions, up to cap_own generated ones).
+
+    Returns dict(q [b,beam,h,k] f32, K_src [b,cap_src,k], V_src, lens_src [b] int32,
+    K_own [b,beam,cap_own,k], V_own, lens_own [b*beam] int32); caches as in random_case.
+    `lens_*`: 'full', 'ragged' (uniform in 1..cap, own part uniform in 0..cap) or explicit."""
+    cfg = 2000 + int(seed)
+    q = _normal(rng(cfg, _S_X), (b, beam, h, k), 1.0 / math.sqrt(k))
+    K_src = _normal(rng(cfg, _S_M), (b, cap_src, k))
+    V_src = _normal(rng(cfg, _S_V), (b, cap_src, v))
+    K_own = _normal(rng(cfg, _S_PK), (b, beam, cap_own, k))
+    V_own = _normal(rng(cfg, _S_PV), (b, beam, cap_own, v))
+
+    def lens_of(spec, n, cap, lowest, stream):
+        if isinstance(spec, str):
+            if spec == "full":
+                return np.full((n,), cap, dtype=np.int32)
+            if spec == "ragged":
+                return rng(cfg, stream).integers(lowest, cap + 1, size=(n,)).astype(np.int32)
+            raise ValueError(spec)
+        return np.asarray(spec, dtype=np.int32).reshape(n)
+
+    ls = lens_of(lens_src, b, cap_src, 1, _S_LENS)
+    lo = lens_of(lens_own, b * beam, cap_own, 0, _S_PICK)
+    if poison:
+        for i in range(b):
+            K_src[i, int(ls[i]):] = np.nan
+            V_src[i, int(ls[i]):] = np.nan
+            for e in range(beam):
+                K_own[i, e, int(lo[i * beam + e]):] = np.nan
+                V_own[i, e, int(lo[i * beam + e]):] = np.nan
+    if cache == "bf16":
+        K_src, V_src, K_own, V_own = (f32_to_bf16_bits(a) for a in (K_src, V_src, K_own, V_own))
+    elif cache != "f32":
+        raise ValueError(cache)
+    return dict(q=q, K_src=K_src, V_src=V_src, lens_src=ls, K_own=K_own, V_own=V_own, lens_own=lo)
+
+
 def cache_as_f64(a: np.ndarray) -> np.ndarray:
     """Cache tensor (uint16 bf16 bits or float32) -> float64 with the same values."""
     if a.dtype == np.uint16:

@@ -17,7 +17,8 @@ MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
 
 EXPORTS = [
     "mqa_project_qkvo", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
-    "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
+    "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention",
+    "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
@@ -58,6 +59,10 @@ def load_library(path: str = LIB_PATH):
     lib.mha_decode_step_window.argtypes = win
     lib.mqa_append_kv_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.mqa_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    lib.mqa_decode_step_beams.argtypes = [vp] * 8 + [ci] * 8 + [cf, vp, sz, vp]
+    lib.mqa_decode_beams_workspace_bytes.argtypes = [ci] * 8
+    lib.mqa_decode_beams_workspace_bytes.restype = sz
+    lib.mqa_beam_reorder_kv.argtypes = [vp] * 7 + [ci] * 6 + [vp]
     lib.mqa_decode_step_ex.argtypes = dec + [tp]
     lib.mha_decode_step_ex.argtypes = dec + [tp]
     lib.mqa_decode_partials.argtypes = dec + [tp]
@@ -77,7 +82,8 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_status_string.argtypes = [ci]
     lib.mqa_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name not in ("mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_status_string"):
+        if name not in ("mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_status_string",
+                        "mqa_decode_beams_workspace_bytes"):
             getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -266,6 +272,59 @@ def mqa_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stre
     if rc != 0:
         raise MqaError("mqa_prefill_attention", rc)
     return o
+
+
+def mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt):
+    return int(load_library().mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt))
+
+
+def mqa_decode_step_beams(q, K_src, V_src, lens_src, K_own, V_own, lens_own, o=None, scale=1.0,
+                          workspace=None, stream=None):
+    """q [b,beam,h,k]; K_src [b,cap_src,k], V_src [b,cap_src,v], lens_src [b]; K_own [b,beam,cap_own,k],
+    V_own [b,beam,cap_own,v], lens_own [b*beam] -> o [b,beam,h,v]."""
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(lens_src, "lens_src", torch.int32), _check(lens_own, "lens_own", torch.int32)
+    for name, t in (("K_src", K_src), ("V_src", V_src), ("K_own", K_own), ("V_own", V_own)):
+        _check(t, name)
+    b, beam, h, k = q.shape
+    cap_src, v = V_src.shape[-2], V_src.shape[-1]
+    cap_own = V_own.shape[-2]
+    if (tuple(K_src.shape) != (b, cap_src, k) or tuple(V_src.shape) != (b, cap_src, v)
+            or tuple(K_own.shape) != (b, beam, cap_own, k) or tuple(V_own.shape) != (b, beam, cap_own, v)
+            or lens_src.numel() != b or lens_own.numel() != b * beam or K_own.dtype != K_src.dtype):
+        raise ValueError("shape mismatch in mqa_decode_step_beams")
+    dt = _cache_dtype(K_src)
+    if o is None:
+        o = torch.empty((b, beam, h, v), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _default_workspace(q.device, mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt))
+    rc = lib.mqa_decode_step_beams(_ptr(q), _ptr(K_src), _ptr(V_src), _ptr(lens_src), _ptr(K_own), _ptr(V_own),
+                                   _ptr(lens_own), _ptr(o), b, beam, h, cap_src, cap_own, k, v, dt, float(scale),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_decode_step_beams", rc)
+    return o
+
+
+def mqa_beam_reorder_kv(K_src, V_src, lens_src, parent, K_dst, V_dst, lens_dst, stream=None):
+    """K_* [n,cap,k] or [n,h_kv,cap,k], V_* likewise, lens_* [n], parent [n] int32: slot r of the
+    destination takes the valid rows and the length of slot parent[r] of the source."""
+    lib = load_library()
+    for name, t in (("K_src", K_src), ("V_src", V_src), ("K_dst", K_dst), ("V_dst", V_dst)):
+        _check(t, name)
+    for name, t in (("lens_src", lens_src), ("parent", parent), ("lens_dst", lens_dst)):
+        _check(t, name, torch.int32)
+    n, cap, k = K_src.shape[0], K_src.shape[-2], K_src.shape[-1]
+    v = V_src.shape[-1]
+    h_kv = K_src.shape[1] if K_src.dim() == 4 else 1
+    if (K_dst.shape != K_src.shape or V_dst.shape != V_src.shape or K_dst.dtype != K_src.dtype
+            or V_src.shape[:-1] != K_src.shape[:-1] or lens_src.numel() != n or parent.numel() != n
+            or lens_dst.numel() != n):
+        raise ValueError("shape mismatch in mqa_beam_reorder_kv")
+    rc = lib.mqa_beam_reorder_kv(_ptr(K_src), _ptr(V_src), _ptr(lens_src), _ptr(parent), _ptr(K_dst), _ptr(V_dst),
+                                 _ptr(lens_dst), n, h_kv, cap, k, v, _cache_dtype(K_src), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_beam_reorder_kv", rc)
 
 
 def mqa_project_qkvo(mode, x, P, out=None, stream=None):

@@ -58,8 +58,24 @@ int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_b
   return MQA_OK;
 }
 
-size_t partial_bytes(long long nseq, int S, int G, int v) {
-  return (size_t)nseq * S * G * (v + 2) * sizeof(float);
+size_t partial_bytes(long long rows, int slots, int v) {
+  return (size_t)rows * slots * (v + 2) * sizeof(float);
+}
+
+void set_partials(DecodeParams* p, void* workspace, long long rows, int slots, int slot0) {
+  p->part_o = static_cast<float*>(workspace);
+  p->part_m = p->part_o ? p->part_o + (size_t)rows * slots * p->v : nullptr;
+  p->part_l = p->part_m ? p->part_m + (size_t)rows * slots : nullptr;
+  p->PS = slots;
+  p->slot0 = slot0;
+}
+
+CombineSegment segment_of(const DecodeParams& p) {
+  CombineSegment sg;
+  sg.lens = p.lens;
+  sg.rows_per_len = p.G * p.lens_div;
+  sg.cap = p.cap; sg.window = p.window; sg.chunk = p.chunk; sg.S = p.S;
+  return sg;
 }
 
 int check_decode_args(const float* q, const void* K, const void* V, const int32_t* lens, const float* o,
@@ -101,17 +117,15 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   if (rc) return rc;
   if (causal_n > 0 && !pl.use_mfma) return MQA_ERR_SHAPE;       // causal rows: MFMA kernel only
   if (pl.S > 1) {
-    if (!workspace || workspace_bytes < partial_bytes(nseq, pl.S, G, v)) return MQA_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < partial_bytes((long long)nseq * G, pl.S, v)) return MQA_ERR_WORKSPACE;
     if (misaligned(workspace)) return MQA_ERR_ALIGN;
   }
   DecodeParams p;
   p.q = q; p.K = K; p.V = V; p.lens = lens; p.o = o;
-  p.part_o = static_cast<float*>(workspace);
-  p.part_m = p.part_o ? p.part_o + (size_t)nseq * pl.S * G * v : nullptr;
-  p.part_l = p.part_m ? p.part_m + (size_t)nseq * pl.S * G : nullptr;
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
   p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? h_true : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
+  set_partials(&p, workspace, (long long)nseq * G, pl.S > 1 ? pl.S : 0, 0);
 #ifdef MQA_TIMELINE
   p.timeline = g_timeline;
 #endif
@@ -122,8 +136,35 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
     if (e != hipSuccess) return MQA_ERR_LAUNCH;
   }
   if ((phase & 2) && pl.S > 1) {
-    if (launch_combine(p, st) != hipSuccess) return MQA_ERR_LAUNCH;
+    CombineParams c;
+    c.part_o = p.part_o; c.part_m = p.part_m; c.part_l = p.part_l; c.o = o;
+    c.rows = (long long)nseq * G; c.v = v; c.PS = pl.S; c.nseg = 1;
+    c.seg[0] = segment_of(p);
+    c.seg[1] = c.seg[0];
+    if (launch_combine(c, st) != hipSuccess) return MQA_ERR_LAUNCH;
   }
+  return MQA_OK;
+}
+
+// Beam search step: the hypotheses of a source attend to the source's shared rows (one launch,
+// beam*h rows per K/V group) and to their own rows (a second launch, h rows per group); the two
+// launches leave partial states in disjoint slots of the same rows and one merge pass finishes.
+struct BeamPlan {
+  Plan src, own;
+  int slots;
+};
+
+int plan_beams(int b, int beam, int h, int cap_src, int cap_own, int k, int v, int dt, BeamPlan* bp) {
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || beam <= 0 || h <= 0 || cap_src <= 0 || cap_own <= 0 || k <= 0 || v <= 0) return MQA_ERR_SHAPE;
+  if ((k & 7) || (v & 7) || k > 256 || v > 256) return MQA_ERR_SHAPE;
+  if ((long long)b * beam * h > (1ll << 24) || cap_src > (1 << 24) || cap_own > (1 << 24)) return MQA_ERR_SHAPE;
+  Tuning tn;
+  int rc = plan_decode(b, beam * h, cap_src, 0, k, v, dt == MQA_BF16, tn, &bp->src);
+  if (rc) return rc;
+  rc = plan_decode(b * beam, h, cap_own, 0, k, v, dt == MQA_BF16, tn, &bp->own);
+  if (rc) return rc;
+  bp->slots = bp->src.S + bp->own.S;
   return MQA_OK;
 }
 
@@ -192,7 +233,7 @@ size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v) {
   if (b <= 0 || h <= 0 || cap <= 0 || v <= 0) return 0;
   int S = (cap + 31) / 32;
   if (S > kMaxSplits) S = kMaxSplits;
-  return partial_bytes(b, S, h, v);
+  return partial_bytes((long long)b * h, S, v);
 }
 
 size_t mha_decode_workspace_bytes(int b, int h, int cap, int v) {
@@ -247,6 +288,75 @@ int mqa_prefill_attention(const float* q, const void* K, const void* V, const in
   if (n <= 0 || n > cap) return MQA_ERR_SHAPE;
   return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
                      nullptr, false, 3, 0, n);
+}
+
+int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, const int32_t* lens_src,
+                          const void* K_own, const void* V_own, const int32_t* lens_own, float* o,
+                          int b, int beam, int h, int cap_src, int cap_own, int k, int v, mqa_dtype dt,
+                          float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !K_src || !V_src || !lens_src || !K_own || !V_own || !lens_own || !o) return MQA_ERR_NULL;
+  BeamPlan bp;
+  int rc = plan_beams(b, beam, h, cap_src, cap_own, k, v, (int)dt, &bp);
+  if (rc) return rc;
+  if (misaligned(q) || misaligned(K_src) || misaligned(V_src) || misaligned(lens_src) || misaligned(K_own) ||
+      misaligned(V_own) || misaligned(lens_own) || misaligned(o))
+    return MQA_ERR_ALIGN;
+  const long long rows = (long long)b * beam * h;
+  if (!workspace || workspace_bytes < partial_bytes(rows, bp.slots, v)) return MQA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return MQA_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DecodeParams ps;
+  ps.q = q; ps.K = K_src; ps.V = V_src; ps.lens = lens_src; ps.o = o;
+  ps.nseq = b; ps.G = beam * h; ps.cap = cap_src; ps.lens_div = 1;
+  ps.k = k; ps.v = v; ps.window = 0; ps.causal_h = 0;
+  ps.chunk = bp.src.chunk; ps.S = bp.src.S; ps.HG = bp.src.HG; ps.merge_alias = 0;
+  ps.qscale = scale * kLog2e;
+  set_partials(&ps, workspace, rows, bp.slots, 0);
+  DecodeParams po = ps;
+  po.K = K_own; po.V = V_own; po.lens = lens_own;
+  po.nseq = b * beam; po.G = h; po.cap = cap_own;
+  po.chunk = bp.own.chunk; po.S = bp.own.S; po.HG = bp.own.HG;
+  po.slot0 = bp.src.S;
+#ifdef MQA_TIMELINE
+  ps.timeline = po.timeline = nullptr;
+#endif
+  hipError_t e = bp.src.use_mfma ? launch_decode_mfma(ps, 0, st) : launch_decode_generic(ps, dt == MQA_BF16, st);
+  if (e != hipSuccess) return MQA_ERR_LAUNCH;
+  e = bp.own.use_mfma ? launch_decode_mfma(po, 0, st) : launch_decode_generic(po, dt == MQA_BF16, st);
+  if (e != hipSuccess) return MQA_ERR_LAUNCH;
+  CombineParams c;
+  c.part_o = ps.part_o; c.part_m = ps.part_m; c.part_l = ps.part_l; c.o = o;
+  c.rows = rows; c.v = v; c.PS = bp.slots; c.nseg = 2;
+  c.seg[0] = segment_of(ps);
+  c.seg[1] = segment_of(po);
+  if (launch_combine(c, st) != hipSuccess) return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
+size_t mqa_decode_beams_workspace_bytes(int b, int beam, int h, int cap_src, int cap_own, int k, int v, mqa_dtype dt) {
+  BeamPlan bp;
+  if (plan_beams(b, beam, h, cap_src, cap_own, k, v, (int)dt, &bp)) return 0;
+  return partial_bytes((long long)b * beam * h, bp.slots, v);
+}
+
+int mqa_beam_reorder_kv(const void* K_src, const void* V_src, const int32_t* lens_src, const int32_t* parent,
+                        void* K_dst, void* V_dst, int32_t* lens_dst,
+                        int n, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream) {
+  if (!K_src || !V_src || !lens_src || !parent || !K_dst || !V_dst || !lens_dst) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (n <= 0 || h_kv <= 0 || cap <= 0 || k <= 0 || v <= 0) return MQA_ERR_SHAPE;
+  if ((k & 7) || (v & 7) || (long long)n * h_kv > (1ll << 24) || cap > (1 << 24)) return MQA_ERR_SHAPE;
+  if (K_src == K_dst || V_src == V_dst || lens_src == lens_dst) return MQA_ERR_SHAPE;     // not an in-place operation
+  if (misaligned(K_src) || misaligned(V_src) || misaligned(K_dst) || misaligned(V_dst) || misaligned(lens_src) ||
+      misaligned(lens_dst) || misaligned(parent))
+    return MQA_ERR_ALIGN;
+  const size_t esz = dt == MQA_BF16 ? 2 : 4;
+  const size_t rowmax = (size_t)(k > v ? k : v) * esz / 16;
+  if (((size_t)cap * rowmax + 4095) / 4096 > 65535) return MQA_ERR_SHAPE;
+  if (launch_reorder(K_src, V_src, lens_src, parent, K_dst, V_dst, lens_dst, n, h_kv, cap, (size_t)k * esz,
+                     (size_t)v * esz, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
 }
 
 int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,

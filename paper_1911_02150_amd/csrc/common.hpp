@@ -19,9 +19,12 @@ struct DecodeParams {
   const void* V;         // [nseq, cap, v]
   const int32_t* lens;   // [nseq / lens_div]
   float* o;              // [nseq, G, v]
-  float* part_o;         // [nseq, S, G, v]  un-normalised partial outputs
-  float* part_m;         // [nseq, S, G]     running maxima (log2 domain)
-  float* part_l;         // [nseq, S, G]     sums of 2^(logit - max)
+  // Partial softmax states, one per (row, slot): row = seq*G + head over the whole call,
+  // slot = slot0 + range.  PS slots per row; PS = 0 means "no partials: write o directly".
+  float* part_o;         // [nseq*G, PS, v]  un-normalised partial outputs
+  float* part_m;         // [nseq*G, PS]     running maxima (log2 domain)
+  float* part_l;         // [nseq*G, PS]     sums of 2^(logit - max)
+  int PS, slot0;
   int nseq, G, cap, lens_div;
   int k, v;
   int window;            // > 0: attend only to the last `window` valid positions (0 = all)
@@ -35,6 +38,24 @@ struct DecodeParams {
 #ifdef MQA_TIMELINE
   long long* timeline;   // debug builds only: [waves][8] wall-clock stamps
 #endif
+};
+
+// The merge of the partial states.  The slots of a row come from up to two launches
+// ("segments": e.g. the memory shared by the hypotheses of a beam and each hypothesis' own
+// rows); a segment wrote slot s only if its range s starts before the row's length there.
+struct CombineSegment {
+  const int32_t* lens;   // length of row r in this segment: lens[r / rows_per_len]
+  int rows_per_len;
+  int cap, window, chunk, S;
+};
+struct CombineParams {
+  const float* part_o;   // [rows, PS, v]
+  const float* part_m;   // [rows, PS]
+  const float* part_l;   // [rows, PS]
+  float* o;              // [rows, v]
+  long long rows;
+  int v, PS, nseg;
+  CombineSegment seg[2]; // segment 0 owns slots [0, seg[0].S), segment 1 the next seg[1].S
 };
 
 struct Tuning {
@@ -52,7 +73,10 @@ hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
 hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t st);
 
 // small_kernels.hip
-hipError_t launch_combine(const DecodeParams& p, hipStream_t st);
+hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_reorder(const void* K_src, const void* V_src, const int32_t* lens_src, const int32_t* parent,
+                          void* K_dst, void* V_dst, int32_t* lens_dst, int n, int h_kv, int cap,
+                          size_t k_row_bytes, size_t v_row_bytes, hipStream_t st);
 hipError_t launch_append(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
                          int b, int h_kv, int cap, int k, int v, int n, int is_bf16, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t st);

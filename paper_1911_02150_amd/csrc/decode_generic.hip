@@ -51,7 +51,7 @@ void decode_generic_kernel(DecodeParams p) {
   const int begin = max(range0, lo);
   const int end = min(range0 + p.chunk, L);
   if (end <= begin) {
-    if (p.S == 1)
+    if (p.PS == 0)
       for (int idx = tid; idx < p.G * v; idx += kThreads) p.o[(size_t)seq * p.G * v + idx] = 0.f;
     return;
   }
@@ -139,17 +139,17 @@ void decode_generic_kernel(DecodeParams p) {
       if (idx < nh * v4) {
         const int hh = idx / v4, c4 = idx - hh * v4;
         float4 a = acc[i];
-        if (p.S == 1) {
+        if (p.PS == 0) {
           const float inv = 1.0f / s_l[hh];
           a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
           reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + h0 + hh) * v)[c4] = a;
         } else {
-          reinterpret_cast<float4*>(p.part_o + (((size_t)seq * p.S + srange) * p.G + h0 + hh) * v)[c4] = a;
+          reinterpret_cast<float4*>(p.part_o + ((((size_t)seq * p.G + h0 + hh) * p.PS) + p.slot0 + srange) * v)[c4] = a;
         }
       }
     }
-    if (p.S > 1 && tid < nh) {
-      const size_t pidx = ((size_t)seq * p.S + srange) * p.G + h0 + tid;
+    if (p.PS > 0 && tid < nh) {
+      const size_t pidx = ((size_t)seq * p.G + h0 + tid) * p.PS + p.slot0 + srange;
       p.part_m[pidx] = s_m[tid];
       p.part_l[pidx] = s_l[tid];
     }

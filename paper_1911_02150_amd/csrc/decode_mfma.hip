@@ -202,7 +202,7 @@ void decode_mfma_kernel(DecodeParams p) {
   const int end = min(begin + p.chunk, lim_max);
   const int mask_from = min(end, lim_min);        // tiles reaching beyond this position need masking
   if (end <= begin) {
-    if (p.S == 1) {           // empty sequence: zero output rows
+    if (p.PS == 0) {          // empty sequence: zero output rows
       for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
         int hl = idx / (kD / 4), c4 = idx % (kD / 4);
         if (head0 + hl < p.G)
@@ -410,12 +410,12 @@ void decode_mfma_kernel(DecodeParams p) {
       lsum += f * lw[it][w];
     }
     const int head = head0 + hl;
-    if (p.S == 1) {
+    if (p.PS == 0) {
       const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;      // (a causal row with nothing to see: zeros)
       a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
       reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * kD)[c4] = a;
     } else {
-      const size_t pidx = ((size_t)seq * p.S + srange) * p.G + head;
+      const size_t pidx = ((size_t)seq * p.G + head) * p.PS + p.slot0 + srange;
       reinterpret_cast<float4*>(p.part_o + pidx * kD)[c4] = a;
       if (c4 == 0) {
         p.part_m[pidx] = M;

@@ -1,80 +1,112 @@
-// Combine pass of the split softmax, cache append, and the two streaming
+// Combine pass of the split softmax, cache append, beam reorder, and the two streaming
 // kernels used as bandwidth references.
 #include "common.hpp"
 
 namespace mqa {
 namespace {
 
-// Merge the partial softmax states of the position ranges of one sequence.
-// With (m_i, l_i, acc_i) the maximum, the sum of 2^(logit - m_i) and the
-// un-normalised weighted sum of V rows over range i (this is the softmax of
-// the paper's Section 2.1 written over a partition of the positions):
+// Merge the partial softmax states of one output row.  With (m_i, l_i, acc_i) the maximum,
+// the sum of 2^(logit - m_i) and the un-normalised weighted sum of V rows over range i (this
+// is the softmax of the paper's Section 2.1 written over a partition of the positions):
 //   M = max_i m_i,  L = sum_i l_i 2^(m_i - M),  o = sum_i acc_i 2^(m_i - M) / L.
-// Only ranges that start before the sequence length were written.
-// SMAX > 0: S <= SMAX known to be small; every partial is fetched up front, independent of
-// the length, so the pass costs one memory latency instead of a chain of three.
+// Only ranges that start before the row's length (per segment) were written.
+// SMAX > 0: PS <= SMAX known to be small; every partial is fetched up front, independent of
+// the lengths, so the pass costs one memory latency instead of a chain of three.
+__device__ __forceinline__ int valid_ranges(const CombineSegment& sg, long long row) {
+  int L = sg.lens[row / sg.rows_per_len];
+  L = L < 0 ? 0 : (L > sg.cap ? sg.cap : L);
+  return min(sg.S, (L - window_base(L, sg.window) + sg.chunk - 1) / sg.chunk);
+}
+
 template <int SMAX>
 __global__ __launch_bounds__(256)
-void combine_kernel(DecodeParams p) {
+void combine_kernel(CombineParams p) {
   const int v4 = p.v >> 2;
-  const size_t total = (size_t)p.nseq * p.G * v4;
+  const size_t total = (size_t)p.rows * v4;
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total) return;
   const int c4 = (int)(idx % v4);
-  const int head = (int)((idx / v4) % p.G);
-  const int seq = (int)(idx / ((size_t)v4 * p.G));
-  const size_t base = (size_t)seq * p.S * p.G + head;
+  const long long row = (long long)(idx / v4);
+  const size_t base = (size_t)row * p.PS;
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  float M = -INFINITY, lsum = 0.f;
   if (SMAX > 0) {
     constexpr int N = SMAX > 0 ? SMAX : 1;
     float pm[N], pl[N];
     float4 po[N];
 #pragma unroll
     for (int s = 0; s < SMAX; ++s) {
-      const size_t pi = base + (size_t)min(s, p.S - 1) * p.G;     // in bounds for every s
+      const size_t pi = base + min(s, p.PS - 1);     // in bounds for every s
       pm[s] = p.part_m[pi];
       pl[s] = p.part_l[pi];
       po[s] = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
     }
-    int L = p.lens[seq / p.lens_div];
-    L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-    const int nvalid = min(p.S, (L - window_base(L, p.window) + p.chunk - 1) / p.chunk);
-    if (nvalid > 0) {
-      float M = -INFINITY;
+    const int n0 = valid_ranges(p.seg[0], row);
+    const int s1 = p.seg[0].S;
+    const int n1 = p.nseg > 1 ? valid_ranges(p.seg[1], row) : 0;
 #pragma unroll
-      for (int s = 0; s < SMAX; ++s)
-        if (s < nvalid) M = fmaxf(M, pm[s]);
-      float lsum = 0.f;
+    for (int s = 0; s < SMAX; ++s)
+      if (s < n0 || (s >= s1 && s < s1 + n1)) M = fmaxf(M, pm[s]);
 #pragma unroll
-      for (int s = 0; s < SMAX; ++s)
-        if (s < nvalid) {            // ranges past the length were never written: skip, do not multiply by 0
-          const float f = __builtin_amdgcn_exp2f(pm[s] - M);
-          a.x += f * po[s].x; a.y += f * po[s].y; a.z += f * po[s].z; a.w += f * po[s].w;
-          lsum += f * pl[s];
-        }
-      const float inv = 1.0f / lsum;
-      a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
-    }
+    for (int s = 0; s < SMAX; ++s)
+      if (s < n0 || (s >= s1 && s < s1 + n1)) {     // unwritten slots are skipped, not multiplied by 0
+        const float f = __builtin_amdgcn_exp2f(pm[s] - M);
+        a.x += f * po[s].x; a.y += f * po[s].y; a.z += f * po[s].z; a.w += f * po[s].w;
+        lsum += f * pl[s];
+      }
   } else {
-    int L = p.lens[seq / p.lens_div];
-    L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
-    const int nvalid = min(p.S, (L - window_base(L, p.window) + p.chunk - 1) / p.chunk);
-    if (nvalid > 0) {
-      float M = -INFINITY;
-      for (int s = 0; s < nvalid; ++s) M = fmaxf(M, p.part_m[base + (size_t)s * p.G]);
-      float lsum = 0.f;
-      for (int s = 0; s < nvalid; ++s) {
-        const size_t pi = base + (size_t)s * p.G;
+    for (int g = 0, s0 = 0; g < p.nseg; s0 += p.seg[g].S, ++g) {
+      const int n = valid_ranges(p.seg[g], row);
+      for (int s = 0; s < n; ++s) M = fmaxf(M, p.part_m[base + s0 + s]);
+    }
+    for (int g = 0, s0 = 0; g < p.nseg; s0 += p.seg[g].S, ++g) {
+      const int n = valid_ranges(p.seg[g], row);
+      for (int s = 0; s < n; ++s) {
+        const size_t pi = base + s0 + s;
         const float f = __builtin_amdgcn_exp2f(p.part_m[pi] - M);
         const float4 x = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
         a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
         lsum += f * p.part_l[pi];
       }
-      const float inv = 1.0f / lsum;
-      a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
     }
   }
-  reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * p.v)[c4] = a;
+  if (lsum > 0.f) {                                 // no valid position at all: a zero row
+    const float inv = 1.0f / lsum;
+    a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
+  }
+  reinterpret_cast<float4*>(p.o + (size_t)row * p.v)[c4] = a;
+}
+
+// Beam search bookkeeping: hypothesis slot r continues hypothesis parent[r], so its cache
+// becomes a copy of that hypothesis' valid rows.  One workgroup per (slot, KV head, 64 KiB piece
+// of the rows); source and destination are different buffers, so slots may be duplicated or
+// dropped freely.  Rows at and beyond the length are not touched.
+__global__ __launch_bounds__(256)
+void reorder_kernel(const uint4* K_src, const uint4* V_src, const int32_t* lens_src, const int32_t* parent,
+                    uint4* K_dst, uint4* V_dst, int32_t* lens_dst, int n, int h_kv, int cap,
+                    int k_row16, int v_row16) {
+  const int r = blockIdx.x / h_kv, j = blockIdx.x % h_kv;
+  int par = parent[r];
+  par = par < 0 ? 0 : (par >= n ? n - 1 : par);
+  int L = lens_src[par];
+  L = L < 0 ? 0 : (L > cap ? cap : L);
+  if (blockIdx.y == 0 && j == 0 && threadIdx.x == 0) lens_dst[r] = L;
+  const size_t piece = 4096;                       // 16-byte words per workgroup and tensor
+  const size_t from = (size_t)blockIdx.y * piece;
+  {
+    const size_t words = (size_t)L * k_row16;
+    const uint4* src = K_src + ((size_t)par * h_kv + j) * cap * k_row16;
+    uint4* dst = K_dst + ((size_t)r * h_kv + j) * cap * k_row16;
+    const size_t to = min(from + piece, words);
+    for (size_t i = from + threadIdx.x; i < to; i += 256) dst[i] = src[i];
+  }
+  {
+    const size_t words = (size_t)L * v_row16;
+    const uint4* src = V_src + ((size_t)par * h_kv + j) * cap * v_row16;
+    uint4* dst = V_dst + ((size_t)r * h_kv + j) * cap * v_row16;
+    const size_t to = min(from + piece, words);
+    for (size_t i = from + threadIdx.x; i < to; i += 256) dst[i] = src[i];
+  }
 }
 
 // In-place form of the listings' concat (Section 2.4 / Section 3): row lens[i]
@@ -134,12 +166,23 @@ void stream_copy_kernel(const uint4* src, uint4* dst, size_t n16) {
 
 }  // namespace
 
-hipError_t launch_combine(const DecodeParams& p, hipStream_t st) {
-  const size_t total = (size_t)p.nseq * p.G * (p.v >> 2);
+hipError_t launch_combine(const CombineParams& p, hipStream_t st) {
+  const size_t total = (size_t)p.rows * (p.v >> 2);
   const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  if (p.S <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
-  else if (p.S <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
+  if (p.PS <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
+  else if (p.PS <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
   else hipLaunchKernelGGL(combine_kernel<0>, grid, block, 0, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_reorder(const void* K_src, const void* V_src, const int32_t* lens_src, const int32_t* parent,
+                          void* K_dst, void* V_dst, int32_t* lens_dst, int n, int h_kv, int cap,
+                          size_t k_row_bytes, size_t v_row_bytes, hipStream_t st) {
+  const size_t row16 = (k_row_bytes > v_row_bytes ? k_row_bytes : v_row_bytes) / 16;
+  const size_t pieces = ((size_t)cap * row16 + 4095) / 4096;
+  const dim3 grid((unsigned)((size_t)n * h_kv), (unsigned)pieces), block(256);
+  hipLaunchKernelGGL(reorder_kernel, grid, block, 0, st, (const uint4*)K_src, (const uint4*)V_src, lens_src, parent,
+                     (uint4*)K_dst, (uint4*)V_dst, lens_dst, n, h_kv, cap, (int)(k_row_bytes / 16), (int)(v_row_bytes / 16));
   return hipGetLastError();
 }
 

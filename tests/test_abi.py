@@ -89,3 +89,34 @@ def test_argument_validation_without_gpu():
     rd = lib.mqa_stream_read
     rd.argtypes = [vp, ctypes.c_size_t, vp, vp]
     assert rd(A, 24, A, None) == 2 and rd(None, 32, A, None) == 1
+
+
+def test_beam_entry_points_validate_without_gpu():
+    import paper_1911_02150_amd as m
+    lib = ctypes.CDLL(LIB)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    A, U = vp(0x10000), vp(0x10004)
+    step = lib.mqa_decode_step_beams
+    step.argtypes = [vp] * 8 + [ci] * 8 + [ctypes.c_float, vp, ctypes.c_size_t, vp]
+    need = m.mqa_decode_beams_workspace_bytes(8, 4, 8, 4096, 128, 128, 128, m.MQA_BF16)
+    # 8 sources x ceil(32 rows / 32) head groups -> 32 ranges over the source, one over the own rows
+    assert need == 8 * 4 * 8 * (32 + 1) * 130 * 4
+    assert m.mqa_decode_beams_workspace_bytes(8, 0, 8, 4096, 128, 128, 128, m.MQA_BF16) == 0
+
+    def call(ptrs=None, sizes=(8, 4, 8, 4096, 128, 128, 128, 1), ws=A, wsb=need):
+        ptrs = ptrs or [A] * 8
+        return step(*ptrs, *sizes, 1.0, ws, wsb, None)
+
+    assert call(ptrs=[A] * 3 + [vp(0)] + [A] * 4) == 1
+    assert call(sizes=(8, 4, 8, 4096, 128, 128, 132, 1)) == 2
+    assert call(sizes=(8, 4, 8, 4096, 128, 128, 128, 7)) == 5
+    assert call(ptrs=[A] * 4 + [U] + [A] * 3) == 3
+    assert call(wsb=need - 1) == 4 and call(ws=vp(0)) == 4
+    re = lib.mqa_beam_reorder_kv
+    re.argtypes = [vp] * 7 + [ci] * 6 + [vp]
+    B = vp(0x20000)
+    assert re(A, A, A, A, B, B, vp(0), 4, 1, 64, 128, 128, 1, None) == 1
+    assert re(A, A, A, A, A, B, B, 4, 1, 64, 128, 128, 1, None) == 2          # in place is refused
+    assert re(A, A, A, A, B, B, B, 4, 1, 64, 128, 124, 1, None) == 2
+    assert re(A, A, A, U, B, B, B, 4, 1, 64, 128, 128, 1, None) == 3
+    assert re(A, A, A, A, B, B, B, 4, 1, 64, 128, 128, 3, None) == 5
