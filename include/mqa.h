@@ -67,7 +67,9 @@ typedef struct {
   int32_t flags;    /* MFMA kernel variants, 0 = default.  bit 0: single bf16 term for
                        q; bit 1: single bf16 term for the softmax weights (both
                        faster, less accurate); bit 2: plain instead of
-                       non-temporal cache loads; bit 4: 8 waves per workgroup   */
+                       non-temporal cache loads; bit 4: 8 waves per workgroup;
+                       bit 5: never, bit 6: always schedule the longest sequences
+                       first (default: only for large ragged-capable batches)    */
 } mqa_tuning;
 
 /*
@@ -101,7 +103,10 @@ int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int3
  * uses scale = 1 (the 1/sqrt(k) factor is folded into P_q or P_k).
  * lens[i] = 0 gives a zero output row.  K, V, q, lens are read only; o is
  * overwritten; `workspace` (>= mqa_decode_workspace_bytes) holds the partial
- * softmax states of the position ranges and is overwritten.
+ * softmax states of the position ranges and is overwritten.  A call that needs
+ * one range per sequence runs without a workspace (NULL, 0); with one, a batch
+ * that has several workgroups per compute unit starts its longest sequences
+ * first (ragged batches finish sooner; outputs are the same either way).
  * The logits and weights never reach memory.
  */
 int mqa_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,

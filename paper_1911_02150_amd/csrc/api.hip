@@ -10,6 +10,10 @@ namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Longest-first scheduling pays once the workgroups outnumber the compute units two to one and the
+// launch is long enough to absorb the ranking pass (~10 us with its launch gap).
+constexpr int kOrderedMinBlocks = 512;
+constexpr long long kOrderedMinBytes = 128ll << 20;
 constexpr int kTargetBlocks = 256;    // one workgroup per compute unit: measured best for the streaming pass
 
 #ifdef MQA_TIMELINE
@@ -126,11 +130,23 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? h_true : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
   set_partials(&p, workspace, (long long)nseq * G, pl.S > 1 ? pl.S : 0, 0);
+  // Ragged batches with several workgroups per compute unit: schedule the longest groups first
+  // (a ranking pass writes the permutation behind the partial states).  Best effort: needs the
+  // workspace; results do not depend on it.
+  const size_t order_off = ((pl.S > 1 ? partial_bytes((long long)nseq * G, pl.S, v) : 0) + 15) & ~(size_t)15;
+  const bool worth_it = (long long)nseq * pl.S * pl.HG >= kOrderedMinBlocks &&
+                        (long long)nseq * cap * (k + v) * 2 >= kOrderedMinBytes;
+  const bool ordered = pl.use_mfma && window == 0 && causal_n == 0 && !(tn.flags & 32) && nseq <= kMaxOrdered &&
+                       (worth_it || (tn.flags & 64)) && workspace && !misaligned(workspace) &&
+                       workspace_bytes >= order_off + (size_t)nseq * sizeof(int32_t);
+  int32_t* order = ordered ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + order_off) : nullptr;
+  p.order = order;
 #ifdef MQA_TIMELINE
   p.timeline = g_timeline;
 #endif
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (phase & 1) {
+    if (order && launch_length_order(lens, p.lens_div, nseq, cap, order, st) != hipSuccess) return MQA_ERR_LAUNCH;
     hipError_t e = pl.use_mfma ? launch_decode_mfma(p, tn.flags, st)
                                : launch_decode_generic(p, dt == MQA_BF16, st);
     if (e != hipSuccess) return MQA_ERR_LAUNCH;
@@ -233,11 +249,13 @@ size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v) {
   if (b <= 0 || h <= 0 || cap <= 0 || v <= 0) return 0;
   int S = (cap + 31) / 32;
   if (S > kMaxSplits) S = kMaxSplits;
-  return partial_bytes((long long)b * h, S, v);
+  return partial_bytes((long long)b * h, S, v) + 16 + (size_t)b * sizeof(int32_t);   // + the schedule of the groups
 }
 
 size_t mha_decode_workspace_bytes(int b, int h, int cap, int v) {
-  return mqa_decode_workspace_bytes(b, h, cap, v);   // b*h groups of one head: same element count
+  if (b <= 0 || h <= 0 || cap <= 0 || v <= 0) return 0;
+  // b*h groups of one head: the same number of partial states, one schedule entry per group
+  return mqa_decode_workspace_bytes(b, h, cap, v) + (size_t)b * (h - 1) * sizeof(int32_t);
 }
 
 int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head,
@@ -308,6 +326,7 @@ int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, 
   DecodeParams ps;
   ps.q = q; ps.K = K_src; ps.V = V_src; ps.lens = lens_src; ps.o = o;
   ps.nseq = b; ps.G = beam * h; ps.cap = cap_src; ps.lens_div = 1;
+  ps.order = nullptr;
   ps.k = k; ps.v = v; ps.window = 0; ps.causal_h = 0;
   ps.chunk = bp.src.chunk; ps.S = bp.src.S; ps.HG = bp.src.HG; ps.merge_alias = 0;
   ps.qscale = scale * kLog2e;

@@ -18,6 +18,7 @@ struct DecodeParams {
   const void* K;         // [nseq, cap, k]
   const void* V;         // [nseq, cap, v]
   const int32_t* lens;   // [nseq / lens_div]
+  const int32_t* order;  // MFMA kernel: null, or a permutation of the groups, longest first (scheduling only)
   float* o;              // [nseq, G, v]
   // Partial softmax states, one per (row, slot): row = seq*G + head over the whole call,
   // slot = slot0 + range.  PS slots per row; PS = 0 means "no partials: write o directly".
@@ -74,6 +75,8 @@ hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t
 
 // small_kernels.hip
 hipError_t launch_combine(const CombineParams& p, hipStream_t st);
+hipError_t launch_length_order(const int32_t* lens, int lens_div, int nseq, int cap, int32_t* order, hipStream_t st);
+constexpr int kMaxOrdered = 1 << 16;      // groups the single-workgroup length ranking handles
 hipError_t launch_reorder(const void* K_src, const void* V_src, const int32_t* lens_src, const int32_t* parent,
                           void* K_dst, void* V_dst, int32_t* lens_dst, int n, int h_kv, int cap,
                           size_t k_row_bytes, size_t v_row_bytes, hipStream_t st);

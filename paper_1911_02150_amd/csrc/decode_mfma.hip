@@ -107,10 +107,23 @@ void decode_mfma_kernel(DecodeParams p) {
 
   // workgroup -> (sequence, range, head group); consecutive work items share an XCD
   const int nb = gridDim.x, bid = blockIdx.x;
-  const int wid = ((nb & 7) == 0) ? (bid & 7) * (nb >> 3) + (bid >> 3) : bid;
-  const int hg = wid % p.HG;
-  const int srange = (wid / p.HG) % p.S;
-  const int seq = wid / (p.HG * p.S);
+  int hg, srange, seq;
+  if (p.order) {
+    // Longest-first schedule: workgroups are dispatched in index order, round-robin over the
+    // 8 XCDs, so XCD x takes the sequences ranked x, x+8, ... by length, longest first, and all
+    // work items of a sequence stay on that XCD.
+    const int j = bid >> 3, items = p.S * p.HG;
+    const int t = (j / items) * 8 + (bid & 7);
+    if (t >= p.nseq) return;                   // padding of the grid to a multiple of 8 sequences
+    hg = j % p.HG;
+    srange = (j / p.HG) % p.S;
+    seq = p.order[t];
+  } else {
+    const int wid = ((nb & 7) == 0) ? (bid & 7) * (nb >> 3) + (bid >> 3) : bid;
+    hg = wid % p.HG;
+    srange = (wid / p.HG) % p.S;
+    seq = wid / (p.HG * p.S);
+  }
   const int head0 = hg * NH;
   int begin = srange * p.chunk;                // < cap by construction of S and chunk; moved up below for a window
 
@@ -429,7 +442,7 @@ void decode_mfma_kernel(DecodeParams p) {
 template <int HB, int NW>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
-  const size_t nblocks = (size_t)p.nseq * p.S * p.HG;
+  const size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
   p.merge_alias = nblocks > 256 ? 1 : 0;      // more workgroups than CUs: keep LDS small
   const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 5 * NW * 16 * HB) * sizeof(float);

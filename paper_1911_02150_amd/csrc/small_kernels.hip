@@ -77,6 +77,38 @@ void combine_kernel(CombineParams p) {
   reinterpret_cast<float4*>(p.o + (size_t)row * p.v)[c4] = a;
 }
 
+// Scheduling aid for ragged batches: a permutation of the KV groups by decreasing length
+// (counting sort over 1024 length classes; the order inside a class is arbitrary, which only
+// affects which workgroup runs when, never a result).  One workgroup.
+__global__ __launch_bounds__(1024)
+void length_order_kernel(const int32_t* lens, int lens_div, int nseq, int cap, int32_t* order) {
+  __shared__ int count[1024];
+  __shared__ int start[1024];
+  const int tid = threadIdx.x;
+  count[tid] = 0;
+  __syncthreads();
+  auto cls = [&](int i) {
+    int L = lens[i / lens_div];
+    L = L < 0 ? 0 : (L > cap ? cap : L);
+    return 1023 - (int)(((long long)L * 1023) / cap);       // class 0 holds the longest
+  };
+  for (int i = tid; i < nseq; i += 1024) atomicAdd(&count[cls(i)], 1);
+  __syncthreads();
+  // exclusive prefix sum over the classes
+  int x = count[tid];
+  start[tid] = x;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int y = tid >= off ? start[tid - off] : 0;
+    __syncthreads();
+    start[tid] += y;
+    __syncthreads();
+  }
+  start[tid] -= x;
+  __syncthreads();
+  for (int i = tid; i < nseq; i += 1024) order[atomicAdd(&start[cls(i)], 1)] = i;
+}
+
 // Beam search bookkeeping: hypothesis slot r continues hypothesis parent[r], so its cache
 // becomes a copy of that hypothesis' valid rows.  One workgroup per (slot, KV head, 64 KiB piece
 // of the rows); source and destination are different buffers, so slots may be duplicated or
@@ -172,6 +204,11 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t st) {
   if (p.PS <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
   else if (p.PS <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
   else hipLaunchKernelGGL(combine_kernel<0>, grid, block, 0, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_length_order(const int32_t* lens, int lens_div, int nseq, int cap, int32_t* order, hipStream_t st) {
+  hipLaunchKernelGGL(length_order_kernel, dim3(1), dim3(1024), 0, st, lens, lens_div, nseq, cap, order);
   return hipGetLastError();
 }
 

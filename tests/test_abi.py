@@ -38,8 +38,9 @@ def test_missing_library_fails_loudly(tmp_path, monkeypatch):
 
 def test_host_side_sizes_and_plan():
     import paper_1911_02150_amd as m
-    assert m.mqa_decode_workspace_bytes(64, 32, 8192, 128) == 64 * 64 * 32 * 130 * 4
-    assert m.mqa_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4
+    assert m.mqa_decode_workspace_bytes(64, 32, 8192, 128) == 64 * 64 * 32 * 130 * 4 + 16 + 64 * 4
+    assert m.mqa_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4 + 16 + 2 * 4
+    assert m.mha_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4 + 16 + 6 * 4
     assert m.mqa_decode_workspace_bytes(0, 3, 40, 8) == 0
     assert m.mqa_decode_num_splits(128, 8, 128, 128, 128, m.MQA_BF16) == 1          # short caches: one range
     assert m.mqa_decode_num_splits(64, 32, 8192, 128, 128, m.MQA_BF16) > 1          # long cache: split

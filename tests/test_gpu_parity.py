@@ -500,3 +500,18 @@ def test_prefill_prompt_then_decode(m):
     K2 = torch.zeros_like(K)
     m.mqa_append_kv_rows(K2, torch.zeros_like(V), kn, vn, lens2)
     assert lens2.cpu().tolist() == [cap - 3, n, n, n] and float(K2[0].float().abs().max()) == 0.0
+
+
+# ----------------------------------------------------------------- longest-first scheduling of ragged batches
+@pytest.mark.parametrize("b,h,cap,multi_head,splits", [(1030, 8, 96, False, 0), (515, 40, 160, False, 0), (5, 8, 300, False, 0),
+                                                       (131, 8, 70, True, 0), (300, 16, 256, False, 4)])
+def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, splits):
+    """Large batches are started longest sequence first (a ranking pass orders the groups; the grid
+    is padded to a multiple of 8 groups); forced here on small ones.  Outputs must equal the
+    oracle's and be bit-identical to the unscheduled launch."""
+    c = mi.random_case(40 + b, b, h, cap, 128, 128, cache="bf16", lens="with_zero", multi_head=multi_head)
+    tn = dict(splits=splits) if splits else {}
+    o, ref = run_case(m, c, multi_head, tuning=dict(tn, flags=64))
+    check(o, ref, "bf16", f"scheduled b={b} h={h}")
+    o_plain, _ = run_case(m, c, multi_head, tuning=dict(tn, flags=32))
+    assert torch.equal(o, o_plain)
