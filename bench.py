@@ -130,7 +130,14 @@ def other_workloads(m, mi, dev):
         kvm = m.MQA_PROJ_KV_MH if mh else m.MQA_PROJ_KV
         dec = m.mha_decode_step if mh else m.mqa_decode_step
 
-        def fn(st):
+        lens2 = torch.empty_like(lens)
+
+        def fn(st):          # three launches: q/k/v projections + append, attention, output projection
+            m.mqa_project_append_qkv(x, Pq, Pk, Pv, K, V, lens, lens2, q=q, stream=st)
+            dec(q, K, V, lens2, o=o, workspace=ws, stream=st)
+            m.mqa_project_qkvo(m.MQA_PROJ_O, o, Po, out=y, stream=st)
+
+        def fn_separate(st):  # the same step through the four separate calls
             m.mqa_project_qkvo(m.MQA_PROJ_Q, x, Pq, out=q, stream=st)
             m.mqa_project_qkvo(kvm, x, Pk, out=kn, stream=st)
             m.mqa_project_qkvo(kvm, x, Pv, out=vn, stream=st)
@@ -140,17 +147,19 @@ def other_workloads(m, mi, dev):
 
         def attn(st):
             dec(q, K, V, lens, o=o, workspace=ws, stream=st)
-        return fn, attn
+        return fn, attn, fn_separate
 
     # workload 1: one fp32 step, b=1, m=128 (projection of the 128-row memory excluded)
-    fn, attn = layer_step_fn(1, 8, 1024, 128, 128, 128, 128, False, torch.float32)
-    out["1_single_step_fp32"] = {"layer_step_us": graph_time_us(fn), "attention_us": graph_time_us(attn)}
+    fn, attn, sep = layer_step_fn(1, 8, 1024, 128, 128, 128, 128, False, torch.float32)
+    out["1_single_step_fp32"] = {"layer_step_us": graph_time_us(fn), "attention_us": graph_time_us(attn),
+                                 "layer_step_separate_calls_us": graph_time_us(sep)}
     # workload 2: b=128, cache of 128 positions, one layer: q/k/v projections, append, attention, output projection
     for mh in (False, True):
-        fn, attn = layer_step_fn(128, 8, 1024, 128, 128, 128, 128, mh, torch.bfloat16)
+        fn, attn, sep = layer_step_fn(128, 8, 1024, 128, 128, 128, 128, mh, torch.bfloat16)
         t, ta = graph_time_us(fn), graph_time_us(attn)
         out["2_incremental_b128_" + ("mha" if mh else "mqa")] = {
-            "layer_step_us": t, "attention_us": ta, "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
+            "layer_step_us": t, "attention_us": ta, "layer_step_separate_calls_us": graph_time_us(sep),
+            "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
     # workload 3: six such layers at 256 cached positions plus feed-forward, final layernorm, logits, argmax
     for mh in (False, True):
         from paper_1911_02150_amd.decoder_stack import DecoderStack

@@ -83,6 +83,22 @@ int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float*
                      int rows, int d, int h, int kv, void* stream);
 
 /*
+ * The first three lines of the incremental listings plus the concat, in one launch: q = x . P_q
+ * is written to q [b,h,k]; the new rows x . P_k, x . P_v go straight into row lens_in[i] of the
+ * caches (rounded as in mqa_append_kv) and lens_out[i] = lens_in[i] + 1.  Same results as
+ * mqa_project_qkvo (Q, KV or KV_MH) followed by mqa_append_kv up to float32 summation order.
+ *   x [b,d]; P_q [h,d,k]; h_kv = 1 (multi-query): P_k [d,k], P_v [d,v], K [b,cap,k], V [b,cap,v];
+ *   h_kv = h (multi-head): P_k [h,d,k], P_v [h,d,v], K [b,h,cap,k], V [b,h,cap,v].
+ *   lens_in and lens_out must be different arrays (the workgroups of the launch read lens_in
+ *   while it runs; MQA_ERR_SHAPE if they are the same pointer); a caller alternates two arrays
+ *   from step to step.  A sequence at capacity keeps its cache and lens_out[i] = lens_in[i].
+ *   d % 8 = 0, k % 16 = 0, v % 16 = 0.
+ */
+int mqa_project_append_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
+                           float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
+                           int b, int d, int h, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream);
+
+/*
  * Cache append: the in-place form of the listings' tf.concat.  For every
  * sequence i with lens[i] < cap, writes k_new[i] / v_new[i] (converted to the
  * cache type, round-to-nearest-even for bf16) as position lens[i] and then

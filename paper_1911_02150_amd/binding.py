@@ -16,7 +16,7 @@ MQA_F32, MQA_BF16 = 0, 1
 MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
 
 EXPORTS = [
-    "mqa_project_qkvo", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
+    "mqa_project_qkvo", "mqa_project_append_qkv", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
     "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
@@ -51,6 +51,7 @@ def load_library(path: str = LIB_PATH):
     tp = ctypes.POINTER(mqa_tuning)
     dec = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
     lib.mqa_project_qkvo.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.mqa_project_append_qkv.argtypes = [vp] * 9 + [ci] * 8 + [vp]
     lib.mqa_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
     lib.mqa_decode_step.argtypes = dec
     lib.mha_decode_step.argtypes = dec
@@ -272,6 +273,32 @@ def mqa_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stre
     if rc != 0:
         raise MqaError("mqa_prefill_attention", rc)
     return o
+
+
+def mqa_project_append_qkv(x, P_q, P_k, P_v, K, V, lens_in, lens_out, q=None, stream=None):
+    """x [b,d], P_q [h,d,k], P_k [d,k] or [h,d,k], P_v likewise, K/V caches, lens_in/lens_out [b] int32
+    (different tensors) -> q [b,h,k]; the new rows are written into the caches."""
+    lib = load_library()
+    for name, t in (("x", x), ("P_q", P_q), ("P_k", P_k), ("P_v", P_v)):
+        _check(t, name, torch.float32)
+    _check(K, "K"), _check(V, "V"), _check(lens_in, "lens_in", torch.int32), _check(lens_out, "lens_out", torch.int32)
+    b, d = x.shape
+    h, _, k = P_q.shape
+    v = P_v.shape[-1]
+    h_kv = P_k.shape[0] if P_k.dim() == 3 else 1
+    cap = K.shape[-2]
+    kshape = (b, cap, k) if K.dim() == 3 else (b, h_kv, cap, k)
+    if (tuple(P_q.shape) != (h, d, k) or tuple(P_k.shape)[-2:] != (d, k) or tuple(P_v.shape)[-2:] != (d, v)
+            or P_v.dim() != P_k.dim() or (K.dim() == 3) != (P_k.dim() == 2) or tuple(K.shape) != kshape
+            or tuple(V.shape) != kshape[:-1] + (v,) or K.dtype != V.dtype or lens_in.numel() != b or lens_out.numel() != b):
+        raise ValueError("shape mismatch in mqa_project_append_qkv")
+    if q is None:
+        q = torch.empty((b, h, k), dtype=torch.float32, device=x.device)
+    rc = lib.mqa_project_append_qkv(_ptr(x), _ptr(P_q), _ptr(P_k), _ptr(P_v), _ptr(q), _ptr(K), _ptr(V), _ptr(lens_in),
+                                    _ptr(lens_out), b, d, h, h_kv, cap, k, v, _cache_dtype(K), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_project_append_qkv", rc)
+    return q
 
 
 def mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt):

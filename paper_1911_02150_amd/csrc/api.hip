@@ -391,6 +391,24 @@ int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float*
   return MQA_OK;
 }
 
+int mqa_project_append_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
+                           float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
+                           int b, int d, int h, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream) {
+  if (!x || !P_q || !P_k || !P_v || !q || !K || !V || !lens_in || !lens_out) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || d <= 0 || h <= 0 || cap <= 0 || k <= 0 || v <= 0) return MQA_ERR_SHAPE;
+  if (h_kv != 1 && h_kv != h) return MQA_ERR_SHAPE;
+  if ((d & 7) || (k & 15) || (v & 15)) return MQA_ERR_SHAPE;
+  if (lens_in == lens_out) return MQA_ERR_SHAPE;
+  if (misaligned(x) || misaligned(P_q) || misaligned(P_k) || misaligned(P_v) || misaligned(q) || misaligned(K) ||
+      misaligned(V) || misaligned(lens_in) || misaligned(lens_out))
+    return MQA_ERR_ALIGN;
+  if (launch_project_qkv_append(x, P_q, P_k, P_v, q, K, V, lens_in, lens_out, b, d, h, h_kv, cap, k, v,
+                                dt == MQA_BF16, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
 int mqa_stream_read(const void* src, size_t bytes, float* sink, void* stream) {
   if (!src || !sink) return MQA_ERR_NULL;
   if (bytes == 0 || (bytes & 15)) return MQA_ERR_SHAPE;

@@ -30,22 +30,21 @@ typedef __attribute__((ext_vector_type(4))) float floatx4;
 constexpr int NWAVES = 8;
 constexpr int GC = 4;        // chunks of contraction indices fetched together
 
-// T = 32: 32x32 tiles (v_mfma_f32_32x32x2_f32, chunks of 8 contraction indices);
-// T = 16: 16x16 tiles (v_mfma_f32_16x16x4_f32, chunks of 16) for GEMMs too small to fill the
-// chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
+// One T x T output tile of out = in . B, left as NWAVES partial tiles in `red` (the caller sums
+// them after the barrier this function ends with).  B is addressed inside P [h, C or N, kv]; n0
+// is the tile's first column (OUT_PROJ: of d; else of h*kv), rows / columns past the end are
+// clamped to the last one and must be discarded by the caller.
 template <bool OUT_PROJ, int T>
-__global__ __launch_bounds__(NWAVES * 64)
-void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* __restrict__ out,
-                         int rows, int d, int h, int kv) {
-  constexpr int TM = T, TN = T;
+__device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const float* __restrict__ P,
+                                          int rows, int d, int h, int kv, int row0, int n0,
+                                          float (*red)[T * T]) {
+  constexpr int TN = T;
   constexpr int CH = 256 / T;                  // contraction indices per chunk (4 per lane group)
   constexpr int NACC = T * T / 64;
-  __shared__ float red[NWAVES][TM * TN];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i32 = lane % T, kk = lane / T;
   const int C = OUT_PROJ ? h * kv : d;
   const int N = OUT_PROJ ? d : h * kv;
-  const int row0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
   const size_t head_stride = (size_t)d * kv;
 
   // A: this lane's row (clamped; rows past the end are discarded at the store)
@@ -123,11 +122,72 @@ void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__
     red[wave][trow * TN + i32] = acc[r];
   }
   __syncthreads();
-  for (int e = tid; e < TM * TN; e += NWAVES * 64) {
-    const int r = e / TN, c = e % TN;
-    if (row0 + r < rows && n0 + c < N)
-      out[(size_t)(row0 + r) * N + n0 + c] = ((red[0][e] + red[1][e]) + (red[2][e] + red[3][e])) +
-                                             ((red[4][e] + red[5][e]) + (red[6][e] + red[7][e]));
+}
+
+__device__ __forceinline__ float sum_partials(const float* red0, int e, int stride) {
+  return ((red0[e] + red0[stride + e]) + (red0[2 * stride + e] + red0[3 * stride + e])) +
+         ((red0[4 * stride + e] + red0[5 * stride + e]) + (red0[6 * stride + e] + red0[7 * stride + e]));
+}
+
+// T = 32: 32x32 tiles (v_mfma_f32_32x32x2_f32, chunks of 8 contraction indices);
+// T = 16: 16x16 tiles (v_mfma_f32_16x16x4_f32, chunks of 16) for GEMMs too small to fill the
+// chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
+template <bool OUT_PROJ, int T>
+__global__ __launch_bounds__(NWAVES * 64)
+void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* __restrict__ out,
+                         int rows, int d, int h, int kv) {
+  __shared__ float red[NWAVES][T * T];
+  const int N = OUT_PROJ ? d : h * kv;
+  const int row0 = blockIdx.y * T, n0 = blockIdx.x * T;
+  gemm_tile<OUT_PROJ, T>(in, P, rows, d, h, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < T * T; e += NWAVES * 64) {
+    const int r = e / T, c = e % T;
+    if (row0 + r < rows && n0 + c < N) out[(size_t)(row0 + r) * N + n0 + c] = sum_partials(&red[0][0], e, T * T);
+  }
+}
+
+template <typename CT> __device__ __forceinline__ CT cache_value(float x);
+template <> __device__ __forceinline__ float cache_value<float>(float x) { return x; }
+template <> __device__ __forceinline__ uint16_t cache_value<uint16_t>(float x) { return (uint16_t)float_to_bf16_rne(x); }
+
+// The first three lines of the incremental listings in one launch: q = x . P_q to memory, the
+// new K and V rows x . P_k, x . P_v straight into row lens_in[i] of the caches (rounded to the
+// cache type), and lens_out[i] = lens_in[i] + 1.  Column tiles are numbered over q's h*k
+// columns, then K's h_kv*k, then V's h_kv*v (k and v are multiples of T, so a tile belongs to
+// one of them).  A sequence at capacity keeps its cache and its length.
+template <int T, typename CT>
+__global__ __launch_bounds__(NWAVES * 64)
+void project_qkv_append_kernel(const float* __restrict__ x, const float* __restrict__ P_q,
+                               const float* __restrict__ P_k, const float* __restrict__ P_v,
+                               float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
+                               const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
+                               int rows, int d, int h, int h_kv, int cap, int k, int v) {
+  __shared__ float red[NWAVES][T * T];
+  const int row0 = blockIdx.y * T;
+  int n0 = blockIdx.x * T;
+  const int nq = h * k, nk = h_kv * k;
+  int which = 0;                       // 0: q, 1: K row, 2: V row
+  if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; }
+  else if (n0 >= nq) { which = 1; n0 -= nq; }
+  const int kv = which == 2 ? v : k;
+  gemm_tile<false, T>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < T * T; e += NWAVES * 64) {
+    const int r = e / T, c = e % T;
+    const int row = row0 + r, n = n0 + c;
+    if (row >= rows) continue;
+    const float val = sum_partials(&red[0][0], e, T * T);
+    if (which == 0) {
+      q[(size_t)row * nq + n] = val;
+    } else {
+      const int L = lens_in[row];
+      if (L < 0 || L >= cap) continue;
+      CT* dst = which == 1 ? K : V;
+      dst[(((size_t)row * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(val);
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < T && row0 + threadIdx.x < rows) {
+    const int L = lens_in[row0 + threadIdx.x];
+    lens_out[row0 + threadIdx.x] = (L < 0 || L >= cap) ? L : L + 1;
   }
 }
 
@@ -148,6 +208,23 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
     if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
     else hipLaunchKernelGGL((project_mfma_kernel<false, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_project_qkv_append(const float* x, const float* P_q, const float* P_k, const float* P_v,
+                                     float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
+                                     int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
+                                     hipStream_t st) {
+  const int ntot = h * k + h_kv * (k + v);
+  const long long tiles32 = (long long)(ntot / 32) * ((rows + 31) / 32);
+  const bool t32 = tiles32 >= 512 && (k % 32) == 0 && (v % 32) == 0;
+  const int T = t32 ? 32 : 16;
+  const dim3 grid(ntot / T, (rows + T - 1) / T), block(NWAVES * 64);
+#define MQA_QKV(TT, CT) hipLaunchKernelGGL((project_qkv_append_kernel<TT, CT>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
+                                           (CT*)K, (CT*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v)
+  if (t32) { if (is_bf16) MQA_QKV(32, uint16_t); else MQA_QKV(32, float); }
+  else     { if (is_bf16) MQA_QKV(16, uint16_t); else MQA_QKV(16, float); }
+#undef MQA_QKV
   return hipGetLastError();
 }
 

@@ -30,6 +30,7 @@ class DecoderStack:
         self.K = [torch.zeros(kshape, dtype=cache_dtype, device=dev) for _ in self.layers]
         self.V = [torch.zeros(vshape, dtype=cache_dtype, device=dev) for _ in self.layers]
         self.lens = [torch.zeros(batch, dtype=torch.int32, device=dev) for _ in self.layers]
+        self._lens_next = [torch.zeros(batch, dtype=torch.int32, device=dev) for _ in self.layers]
 
     # -- pieces, so that a test can look between them
     def embed(self, tokens: torch.Tensor, t: int) -> torch.Tensor:
@@ -46,6 +47,15 @@ class DecoderStack:
         vn = B.mqa_project_qkvo(mode, hx, w["P_v"])
         B.mqa_append_kv(self.K[l], self.V[l], kn, vn, self.lens[l])
         return q, kn, vn
+
+    def attention_append_fused(self, l: int, x: torch.Tensor) -> torch.Tensor:
+        """LN, then q and the append of the new K/V rows in one launch.  Returns q."""
+        w = self.layers[l]
+        hx = B.mqa_stack_layernorm(x)
+        q = B.mqa_project_append_qkv(hx, w["P_q"], w["P_k"], w["P_v"], self.K[l], self.V[l], self.lens[l],
+                                     self._lens_next[l])
+        self.lens[l], self._lens_next[l] = self._lens_next[l], self.lens[l]      # the lengths alternate between two arrays
+        return q
 
     def attention_attend(self, l: int, q: torch.Tensor) -> torch.Tensor:
         """Attention over the cache and the output projection.  Returns y."""
@@ -68,7 +78,7 @@ class DecoderStack:
     def step(self, tokens: torch.Tensor, t: int) -> torch.Tensor:
         x = self.embed(tokens, t)
         for l in range(len(self.layers)):
-            q, _, _ = self.attention_append(l, x)
+            q = self.attention_append_fused(l, x)
             B.mqa_stack_add(x, self.attention_attend(l, q))
             B.mqa_stack_add(x, self.feed_forward(l, x))
         return self.logits(x)

@@ -515,3 +515,55 @@ def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, spli
     check(o, ref, "bf16", f"scheduled b={b} h={h}")
     o_plain, _ = run_case(m, c, multi_head, tuning=dict(tn, flags=32))
     assert torch.equal(o, o_plain)
+
+
+# ----------------------------------------------------------------- q, K row, V row and the append in one launch
+@pytest.mark.parametrize("b,d,h,k,v,cap,cache,mh", [
+    (128, 1024, 8, 128, 128, 40, "bf16", False),      # workload 2's shape: 16x16 tiles
+    (128, 1024, 8, 128, 128, 40, "bf16", True),
+    (512, 256, 8, 128, 64, 9, "bf16", False),         # enough tiles for the 32x32 variant
+    (5, 72, 3, 48, 16, 7, "f32", False),
+    (33, 136, 4, 32, 32, 5, "f32", True),
+])
+def test_fused_qkv_projection_and_append(m, b, d, h, k, v, cap, cache, mh):
+    g = mi.rng(3300, b + d)
+    x = g.standard_normal((b, d), dtype=np.float32)
+    P_q = g.standard_normal((h, d, k), dtype=np.float32) / np.float32(np.sqrt(d))
+    P_k = g.standard_normal((h, d, k) if mh else (d, k), dtype=np.float32) / np.float32(np.sqrt(d))
+    P_v = g.standard_normal((h, d, v) if mh else (d, v), dtype=np.float32) / np.float32(np.sqrt(d))
+    lens = g.integers(0, cap + 1, size=b).astype(np.int32)
+    lens[0], lens[b - 1] = cap, 0                      # one sequence at capacity: untouched
+    tdt = torch.bfloat16 if cache == "bf16" else torch.float32
+    kshape = (b, h, cap, k) if mh else (b, cap, k)
+    K = torch.full(kshape, 3.0, dtype=tdt, device=DEV)
+    V = torch.full(kshape[:-1] + (v,), 3.0, dtype=tdt, device=DEV)
+    lens_in = torch.from_numpy(lens).to(DEV)
+    lens_out = torch.full((b,), -7, dtype=torch.int32, device=DEV)
+    q = m.mqa_project_append_qkv(*(torch.from_numpy(a).to(DEV) for a in (x, P_q, P_k, P_v)), K, V, lens_in, lens_out)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(q.cpu().numpy() - orc.project_q(x, P_q))) <= 1e-5
+    assert np.array_equal(lens_out.cpu().numpy(), np.where(lens < cap, lens + 1, lens))
+    assert np.array_equal(lens_in.cpu().numpy(), lens)
+    k_exact = orc.project_kv_mh(x, P_k) if mh else orc.project_kv(x, P_k)
+    v_exact = orc.project_kv_mh(x, P_v) if mh else orc.project_kv(x, P_v)
+    rnd = orc.round_to_bf16 if cache == "bf16" else orc.round_to_f32
+    for got, exact in ((K.double().cpu().numpy(), k_exact), (V.double().cpu().numpy(), v_exact)):
+        for i in range(b):
+            L = int(lens[i])
+            rows = np.delete(got[i], L, axis=-2) if L < cap else got[i]
+            assert (rows == 3.0).all(), "a row other than the appended one was written"
+            if L < cap:
+                new = got[i, ..., L, :]
+                # the stored value is the cache rounding of a float32 sum within 2e-5 of the exact one
+                assert (new >= rnd(exact[i] - 2e-5)).all() and (new <= rnd(exact[i] + 2e-5)).all()
+    # the same through the separate calls: equal up to float32 summation order, then one rounding
+    K2, V2 = torch.full_like(K, 3.0), torch.full_like(V, 3.0)
+    l2 = lens_in.clone()
+    mode = m.MQA_PROJ_KV_MH if mh else m.MQA_PROJ_KV
+    dx = torch.from_numpy(x).to(DEV)
+    m.mqa_append_kv(K2, V2, m.mqa_project_qkvo(mode, dx, torch.from_numpy(P_k).to(DEV)),
+                    m.mqa_project_qkvo(mode, dx, torch.from_numpy(P_v).to(DEV)), l2)
+    assert torch.equal(l2, lens_out)
+    ulp = 2.0 ** -7 if cache == "bf16" else 1e-5
+    assert float((K2.float() - K.float()).abs().max()) <= ulp * float(K.float().abs().max())
+    assert float(((K2.float() - K.float()) != 0).float().mean()) < 1e-2
