@@ -8,7 +8,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmqa_decode.so")
-SOURCES = ["api.hip", "decode_mfma.hip", "decode_generic.hip", "small_kernels.hip", "project.hip", "stack_kernels.hip"]
+SOURCES = ["api.hip", "decode_mfma.hip", "decode_generic.hip", "small_kernels.hip", "project.hip", "gemm.hip", "stack_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

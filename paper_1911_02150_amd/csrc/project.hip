@@ -195,6 +195,8 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
 
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, hipStream_t st) {
+  const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, st);     // large GEMMs: LDS-tiled kernel
+  if (big != hipErrorNotSupported) return big;
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
   const long long tiles32 = (long long)((N + 31) / 32) * ((rows + 31) / 32);

@@ -162,3 +162,44 @@ def test_beam_search_loop(m):
     assert np.array_equal(lens.cpu().numpy(), rlens) and int(rlens[0]) == steps
     for r in range(n):
         assert np.array_equal(K[r, :steps].double().cpu().numpy(), rK[r, :steps])
+
+
+def test_encoder_decoder_memory_with_beams(m):
+    """Encoder-decoder attention (Section 3 `MultiqueryAttention`: queries against a static memory M)
+    under beam search: the memory rows of a source are projected once, its `beam` hypotheses are
+    beam*h rows of one multi-query call over that fixed cache.  The cache holds the oracle's
+    bf16-rounded K/V rows (oracle -> GPU), so the stated tolerance applies to y."""
+    b, beam, h, d, k, v, cap = 6, 4, 8, 256, 128, 128, 100
+    g = mi.rng(2300, 0)
+    s = np.float32(d ** -0.5)
+    x = g.standard_normal((b, beam, d), dtype=np.float32)
+    M = g.standard_normal((b, cap, d), dtype=np.float32)
+    P_q = g.standard_normal((h, d, k), dtype=np.float32) * s
+    P_k = g.standard_normal((d, k), dtype=np.float32) * s
+    P_v = g.standard_normal((d, v), dtype=np.float32) * s
+    P_o = g.standard_normal((h, d, v), dtype=np.float32) * np.float32((h * v) ** -0.5)
+    mlen = g.integers(1, cap + 1, size=b).astype(np.int32)
+    Kr = orc.round_to_bf16(orc.project_kv(M.reshape(b * cap, d), P_k)).reshape(b, cap, k)
+    Vr = orc.round_to_bf16(orc.project_kv(M.reshape(b * cap, d), P_v)).reshape(b, cap, v)
+    ref = np.zeros((b, beam, d))
+    for i in range(b):
+        for e in range(beam):
+            qi = orc.project_q(x[i, e][None], P_q)[0]
+            o = orc.mqa_decode(qi[None], Kr[i][None], Vr[i][None], [mlen[i]])
+            ref[i, e] = orc.project_o(o, P_o)[0]
+    dx = torch.from_numpy(x).to(DEV).view(b * beam, d)
+    q = m.mqa_project_qkvo(m.MQA_PROJ_Q, dx, torch.from_numpy(P_q).to(DEV))               # [b*beam, h, k]
+    K = torch.from_numpy(Kr).to(torch.bfloat16).to(DEV)
+    V = torch.from_numpy(Vr).to(torch.bfloat16).to(DEV)
+    o = m.mqa_decode_step(q.view(b, beam * h, k), K, V, torch.from_numpy(mlen).to(DEV))     # beam*h rows per source
+    y = m.mqa_project_qkvo(m.MQA_PROJ_O, o.view(b * beam, h, v), torch.from_numpy(P_o).to(DEV))
+    torch.cuda.synchronize()
+    check(y.view(b, beam, d), ref, "bf16", "encoder-decoder attention, beam 4")
+    # the GPU's own projection of the memory, appended in bulk, gives valid roundings of the same rows
+    kn = m.mqa_project_qkvo(m.MQA_PROJ_KV, torch.from_numpy(M).to(DEV).view(b * cap, d), torch.from_numpy(P_k).to(DEV))
+    vn = m.mqa_project_qkvo(m.MQA_PROJ_KV, torch.from_numpy(M).to(DEV).view(b * cap, d), torch.from_numpy(P_v).to(DEV))
+    K2, V2 = torch.zeros_like(K), torch.zeros_like(V)
+    l2 = torch.zeros(b, dtype=torch.int32, device=DEV)
+    m.mqa_append_kv_rows(K2, V2, kn.view(b, cap, k), vn.view(b, cap, v), l2)
+    assert int(l2.min()) == cap and float((K2.float() - K.float()).abs().max()) <= 2.0 ** -6
+    assert float((K2 != K).float().mean()) < 1e-2
