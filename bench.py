@@ -161,23 +161,26 @@ def other_workloads(m, mi, dev):
             "layer_step_us": t, "attention_us": ta, "layer_step_separate_calls_us": graph_time_us(sep),
             "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
     # workload 3: six such layers at 256 cached positions plus feed-forward, final layernorm, logits, argmax
-    for mh in (False, True):
+    # (b = 1024 is the paper's whole batch, which it spread over 8 TPU cores, on the one GPU)
+    for mh, bsz in ((False, None), (True, None), (False, 1024), (True, 1024)):
         from paper_1911_02150_amd.decoder_stack import DecoderStack
         cfg = mi.CONFIGS[3]
+        bsz = bsz or cfg["b"]
         w = mi.config3_weights(cfg["layers"], cfg["d"], cfg["h"], cfg["k"], cfg["v"], cfg["d_ff"], cfg["vocab"],
                                cfg["cap"], mh)
-        st_ = DecoderStack(w, cfg["b"], cfg["cap"], mh, dev)
+        st_ = DecoderStack(w, bsz, cfg["cap"], mh, dev)
         for l in range(cfg["layers"]):
             st_.lens[l].fill_(cfg["cap"])
-        tok = torch.zeros(cfg["b"], dtype=torch.int32, device=dev)
+            st_._lens_next[l].fill_(cfg["cap"])
+        tok = torch.zeros(bsz, dtype=torch.int32, device=dev)
 
         def full(stream):
             with torch.cuda.stream(stream) if stream is not None else torch.cuda.stream(torch.cuda.current_stream()):
                 st_.greedy(st_.step(tok, cfg["cap"] - 1))
         t = graph_time_us(full, replays=10, repeat=3)
-        out["3_decoder_stack_" + ("mha" if mh else "mqa")] = {
-            "step_us": t, "us_per_token": t / cfg["b"], "tokens_per_s": cfg["b"] / (t * 1e-6),
-            "cached_positions": cfg["cap"], "layers": cfg["layers"]}
+        name = "3_decoder_stack_" + ("mha" if mh else "mqa") + ("" if bsz == cfg["b"] else f"_b{bsz}")
+        out[name] = {"step_us": t, "us_per_token": t / bsz, "tokens_per_s": bsz / (t * 1e-6), "b": bsz,
+                     "cached_positions": cfg["cap"], "layers": cfg["layers"]}
         del st_, w
     # beam-4 decoding at workload 2's shape: 128 sources, 128 shared + 128 own positions per hypothesis;
     # against the same step over per-hypothesis copies of the memory (multi-query and multi-head), and the
