@@ -182,37 +182,40 @@ def other_workloads(m, mi, dev):
         out[name] = {"step_us": t, "us_per_token": t / bsz, "tokens_per_s": bsz / (t * 1e-6), "b": bsz,
                      "cached_positions": cfg["cap"], "layers": cfg["layers"]}
         del st_, w
-    # beam-4 decoding at workload 2's shape: 128 sources, 128 shared + 128 own positions per hypothesis;
-    # against the same step over per-hypothesis copies of the memory (multi-query and multi-head), and the
-    # per-step cache reorder for the two cache layouts
-    b, beam, h, cs, co = 128, 4, 8, 128, 128
-    n = b * beam
-    bf = torch.bfloat16
-    q = torch.randn(b, beam, h, 128, device=dev) / 128 ** 0.5
-    o = torch.empty(b, beam, h, 128, device=dev)
-    Ksrc, Vsrc = torch.randn(b, cs, 128, device=dev).to(bf), torch.randn(b, cs, 128, device=dev).to(bf)
-    Kown, Vown = torch.randn(b, beam, co, 128, device=dev).to(bf), torch.randn(b, beam, co, 128, device=dev).to(bf)
-    lsrc = torch.full((b,), cs, dtype=torch.int32, device=dev)
-    lown = torch.full((n,), co, dtype=torch.int32, device=dev)
-    ws = torch.empty(m.mqa_decode_beams_workspace_bytes(b, beam, h, cs, co, 128, 128, m.MQA_BF16), dtype=torch.uint8, device=dev)
-    t_beams = graph_time_us(lambda st: m.mqa_decode_step_beams(q, Ksrc, Vsrc, lsrc, Kown, Vown, lown, o=o, workspace=ws, stream=st))
-    Kf, Vf = torch.randn(n, cs + co, 128, device=dev).to(bf), torch.randn(n, cs + co, 128, device=dev).to(bf)
-    lf = torch.full((n,), cs + co, dtype=torch.int32, device=dev)
-    wsf = torch.empty(m.mqa_decode_workspace_bytes(n, h, cs + co, 128), dtype=torch.uint8, device=dev)
-    qf, of = q.view(n, h, 128), o.view(n, h, 128)
-    t_flat = graph_time_us(lambda st: m.mqa_decode_step(qf, Kf, Vf, lf, o=of, workspace=wsf, stream=st))
-    Kh, Vh = torch.randn(n, h, cs + co, 128, device=dev).to(bf), torch.randn(n, h, cs + co, 128, device=dev).to(bf)
-    t_mha = graph_time_us(lambda st: m.mha_decode_step(qf, Kh, Vh, lf, o=of, workspace=wsf, stream=st))
-    parent = ((torch.arange(n, device=dev) // beam) * beam + torch.randint(0, beam, (n,), device=dev)).to(torch.int32)
-    K2, V2, l2 = torch.empty_like(Kown), torch.empty_like(Vown), torch.empty_like(lown)
-    t_re = graph_time_us(lambda st: m.mqa_beam_reorder_kv(Kown.view(n, co, 128), Vown.view(n, co, 128), lown, parent,
-                                                          K2.view(n, co, 128), V2.view(n, co, 128), l2, stream=st))
-    Kh2, Vh2 = torch.empty_like(Kh), torch.empty_like(Vh)
-    t_re_mha = graph_time_us(lambda st: m.mqa_beam_reorder_kv(Kh, Vh, lf, parent, Kh2, Vh2, l2, stream=st))
-    out["beam4_b128_src128_own128"] = {
-        "mqa_shared_source_attention_us": t_beams, "mqa_per_hypothesis_copies_attention_us": t_flat,
-        "mha_attention_us": t_mha, "mqa_reorder_own_rows_us": t_re, "mha_reorder_whole_cache_us": t_re_mha}
-    del Kh, Vh, Kh2, Vh2, Kf, Vf
+    # beam-4 decoding: (a) workload 2's shape, 128 sources, 128 shared + 128 own positions per hypothesis;
+    # (b) long prompts, 16 sources, 8192 shared + 128 own.  Against the same step over per-hypothesis copies of
+    # the memory (multi-query and multi-head), and the per-step cache reorder for the two cache layouts.
+    def beam_case(b, beam, h, cs, co, with_mha):
+        n = b * beam
+        bf = torch.bfloat16
+        q = torch.randn(b, beam, h, 128, device=dev) / 128 ** 0.5
+        o = torch.empty(b, beam, h, 128, device=dev)
+        Ksrc, Vsrc = torch.randn(b, cs, 128, device=dev).to(bf), torch.randn(b, cs, 128, device=dev).to(bf)
+        Kown, Vown = torch.randn(b, beam, co, 128, device=dev).to(bf), torch.randn(b, beam, co, 128, device=dev).to(bf)
+        lsrc = torch.full((b,), cs, dtype=torch.int32, device=dev)
+        lown = torch.full((n,), co, dtype=torch.int32, device=dev)
+        ws = torch.empty(m.mqa_decode_beams_workspace_bytes(b, beam, h, cs, co, 128, 128, m.MQA_BF16), dtype=torch.uint8, device=dev)
+        r = {"mqa_shared_source_attention_us": graph_time_us(
+            lambda st: m.mqa_decode_step_beams(q, Ksrc, Vsrc, lsrc, Kown, Vown, lown, o=o, workspace=ws, stream=st))}
+        Kf, Vf = torch.randn(n, cs + co, 128, device=dev).to(bf), torch.randn(n, cs + co, 128, device=dev).to(bf)
+        lf = torch.full((n,), cs + co, dtype=torch.int32, device=dev)
+        wsf = torch.empty(m.mqa_decode_workspace_bytes(n, h, cs + co, 128), dtype=torch.uint8, device=dev)
+        qf, of = q.view(n, h, 128), o.view(n, h, 128)
+        r["mqa_per_hypothesis_copies_attention_us"] = graph_time_us(
+            lambda st: m.mqa_decode_step(qf, Kf, Vf, lf, o=of, workspace=wsf, stream=st))
+        parent = ((torch.arange(n, device=dev) // beam) * beam + torch.randint(0, beam, (n,), device=dev)).to(torch.int32)
+        K2, V2, l2 = torch.empty_like(Kown), torch.empty_like(Vown), torch.empty_like(lown)
+        r["mqa_reorder_own_rows_us"] = graph_time_us(
+            lambda st: m.mqa_beam_reorder_kv(Kown.view(n, co, 128), Vown.view(n, co, 128), lown, parent,
+                                             K2.view(n, co, 128), V2.view(n, co, 128), l2, stream=st))
+        if with_mha:
+            Kh, Vh = torch.randn(n, h, cs + co, 128, device=dev).to(bf), torch.randn(n, h, cs + co, 128, device=dev).to(bf)
+            r["mha_attention_us"] = graph_time_us(lambda st: m.mha_decode_step(qf, Kh, Vh, lf, o=of, workspace=wsf, stream=st))
+            Kh2, Vh2 = torch.empty_like(Kh), torch.empty_like(Vh)
+            r["mha_reorder_whole_cache_us"] = graph_time_us(lambda st: m.mqa_beam_reorder_kv(Kh, Vh, lf, parent, Kh2, Vh2, l2, stream=st))
+        return r
+    out["beam4_b128_src128_own128"] = beam_case(128, 4, 8, 128, 128, True)
+    out["beam4_b16_src8192_own128"] = beam_case(16, 4, 8, 8192, 128, False)
     # workload 5: ragged batch, attention only
     cfg = mi.CONFIGS[5]
     b, h, cap = cfg["b"], cfg["h"], cfg["cap"]

@@ -10,15 +10,16 @@ namespace {
 // is the softmax of the paper's Section 2.1 written over a partition of the positions):
 //   M = max_i m_i,  L = sum_i l_i 2^(m_i - M),  o = sum_i acc_i 2^(m_i - M) / L.
 // Only ranges that start before the row's length (per segment) were written.
-// SMAX > 0: PS <= SMAX known to be small; every partial is fetched up front, independent of
-// the lengths, so the pass costs one memory latency instead of a chain of three.
+// The slots of a row are fetched B at a time, all loads of a batch issued before any is used
+// and independent of the lengths, so a batch costs one memory latency; batches are folded
+// into a running (M, L, o) state.  B = 4 covers the usual 2..4 ranges in one batch.
 __device__ __forceinline__ int valid_ranges(const CombineSegment& sg, long long row) {
   int L = sg.lens[row / sg.rows_per_len];
   L = L < 0 ? 0 : (L > sg.cap ? sg.cap : L);
   return min(sg.S, (L - window_base(L, sg.window) + sg.chunk - 1) / sg.chunk);
 }
 
-template <int SMAX>
+template <int B>
 __global__ __launch_bounds__(256)
 void combine_kernel(CombineParams p) {
   const int v4 = p.v >> 2;
@@ -28,47 +29,41 @@ void combine_kernel(CombineParams p) {
   const int c4 = (int)(idx % v4);
   const long long row = (long long)(idx / v4);
   const size_t base = (size_t)row * p.PS;
+  const int n0 = valid_ranges(p.seg[0], row);
+  const int s1 = p.seg[0].S;
+  const int n1 = p.nseg > 1 ? valid_ranges(p.seg[1], row) : 0;
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   float M = -INFINITY, lsum = 0.f;
-  if (SMAX > 0) {
-    constexpr int N = SMAX > 0 ? SMAX : 1;
-    float pm[N], pl[N];
-    float4 po[N];
+  for (int sb = 0; sb < p.PS; sb += B) {
+    float pm[B], pl[B];
+    float4 po[B];
 #pragma unroll
-    for (int s = 0; s < SMAX; ++s) {
-      const size_t pi = base + min(s, p.PS - 1);     // in bounds for every s
-      pm[s] = p.part_m[pi];
-      pl[s] = p.part_l[pi];
-      po[s] = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
+    for (int j = 0; j < B; ++j) {
+      const size_t pi = base + min(sb + j, p.PS - 1);     // in bounds for every j
+      pm[j] = p.part_m[pi];
+      pl[j] = p.part_l[pi];
+      po[j] = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
     }
-    const int n0 = valid_ranges(p.seg[0], row);
-    const int s1 = p.seg[0].S;
-    const int n1 = p.nseg > 1 ? valid_ranges(p.seg[1], row) : 0;
+    bool ok[B];
+    float Mn = M;
 #pragma unroll
-    for (int s = 0; s < SMAX; ++s)
-      if (s < n0 || (s >= s1 && s < s1 + n1)) M = fmaxf(M, pm[s]);
+    for (int j = 0; j < B; ++j) {
+      const int sl = sb + j;                              // unwritten slots are skipped, not multiplied by 0
+      ok[j] = sl < p.PS && (sl < n0 || (sl >= s1 && sl < s1 + n1));
+      if (ok[j]) Mn = fmaxf(Mn, pm[j]);
+    }
+    if (Mn == -INFINITY) continue;
+    const float f0 = __builtin_amdgcn_exp2f(M - Mn);      // 0 while nothing has been folded in yet
+    a.x *= f0; a.y *= f0; a.z *= f0; a.w *= f0;
+    lsum *= f0;
 #pragma unroll
-    for (int s = 0; s < SMAX; ++s)
-      if (s < n0 || (s >= s1 && s < s1 + n1)) {     // unwritten slots are skipped, not multiplied by 0
-        const float f = __builtin_amdgcn_exp2f(pm[s] - M);
-        a.x += f * po[s].x; a.y += f * po[s].y; a.z += f * po[s].z; a.w += f * po[s].w;
-        lsum += f * pl[s];
+    for (int j = 0; j < B; ++j)
+      if (ok[j]) {
+        const float f = __builtin_amdgcn_exp2f(pm[j] - Mn);
+        a.x += f * po[j].x; a.y += f * po[j].y; a.z += f * po[j].z; a.w += f * po[j].w;
+        lsum += f * pl[j];
       }
-  } else {
-    for (int g = 0, s0 = 0; g < p.nseg; s0 += p.seg[g].S, ++g) {
-      const int n = valid_ranges(p.seg[g], row);
-      for (int s = 0; s < n; ++s) M = fmaxf(M, p.part_m[base + s0 + s]);
-    }
-    for (int g = 0, s0 = 0; g < p.nseg; s0 += p.seg[g].S, ++g) {
-      const int n = valid_ranges(p.seg[g], row);
-      for (int s = 0; s < n; ++s) {
-        const size_t pi = base + s0 + s;
-        const float f = __builtin_amdgcn_exp2f(p.part_m[pi] - M);
-        const float4 x = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
-        a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
-        lsum += f * p.part_l[pi];
-      }
-    }
+    M = Mn;
   }
   if (lsum > 0.f) {                                 // no valid position at all: a zero row
     const float inv = 1.0f / lsum;
@@ -202,8 +197,7 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t st) {
   const size_t total = (size_t)p.rows * (p.v >> 2);
   const dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (p.PS <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
-  else if (p.PS <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
-  else hipLaunchKernelGGL(combine_kernel<0>, grid, block, 0, st, p);
+  else hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
   return hipGetLastError();
 }
 
