@@ -288,6 +288,24 @@ def beam_reorder_kv(K, V, lens, parent):
     return K2, V2, lens2
 
 
+def mha_prefill(q, K, V, lens, scale=1.0):
+    """Attention of the Section 2.3 batched listing (`MultiheadAttentionBatched`) with its causal
+    mask, for n consecutive queries per sequence against per-head caches that already hold their
+    rows: q [b,h,n,k], K [b,h,cap,k], V [b,h,cap,v]; query j of sequence i sits at position
+    lens[i]-n+j and attends to positions 0..lens[i]-n+j of its own head.  Returns o [b,h,n,v]."""
+    q, K, V = (np.asarray(a, dtype=F64) for a in (q, K, V))
+    b, h, n, _ = q.shape
+    o = np.zeros((b, h, n, V.shape[-1]), dtype=F64)
+    for i in range(b):
+        L = int(lens[i])
+        pos = L - n + np.arange(n)
+        mask = np.where(np.arange(L)[None, :] <= pos[:, None], 0.0, -np.inf)      # [n, L]
+        for j in range(h):
+            logits = scale * np.einsum("nk,mk->nm", q[i, j], K[i, j, :L], optimize=True)
+            o[i, j] = np.einsum("nm,mv->nv", softmax64(logits + mask), V[i, j, :L], optimize=True)
+    return o
+
+
 def mha_decode(q, K, V, lens, scale=1.0, window=None):
     """Attention part of `MultiheadSelfAttentionIncremental` (Section 2.4):
     logits = einsum('bhk,bhmk->bhm'), softmax, o = einsum('bhm,bhmv->bhv').

@@ -70,6 +70,8 @@ MFMA_CASES = [
     (8, 2, 32, 4100, "full", 0),           # heuristics choose the split
     (9, 6, 8, 33, [1, 2, 31, 32, 33, 17], 0),
     (10, 2, 40, 64, "with_zero", 2),
+    (11, 1, 8, 4096, "ragged", 64),        # the maximum number of ranges: the merge folds 8 batches of slots
+    (12, 2, 32, 2500, "ragged", 20),
 ]
 
 

@@ -376,6 +376,34 @@ def test_prefill_equals_stepwise_decode_and_batched_listing():
     assert np.max(np.abs(Y - ref)) <= 1e-12
 
 
+def test_mha_prefill_pins():
+    g = _rng(33)
+    b, n, h, k, v, d = 2, 6, 3, 4, 5, 7
+    prefix = [0, 3]
+    cap = n + 4
+    K, V = g.normal(size=(b, h, cap, k)), g.normal(size=(b, h, cap, v))
+    q = g.normal(size=(b, h, n, k))
+    lens = [prefix[0] + n, prefix[1] + n]
+    got = orc.mha_prefill(q, K, V, lens, scale=1.3)
+    for i in range(b):
+        for j in range(n):                           # one query at a time through the pinned multi-head step
+            ref = orc.mha_decode(q[i:i + 1, :, j], K[i:i + 1], V[i:i + 1], [prefix[i] + j + 1], scale=1.3)
+            assert np.max(np.abs(got[i, :, j] - ref[0])) <= 1e-14
+    # every head reading the same K/V: the multi-query prefill (other q layout)
+    Ks, Vs = K[:, 0], V[:, 0]
+    same = orc.mha_prefill(q, np.repeat(Ks[:, None], h, 1), np.repeat(Vs[:, None], h, 1), lens)
+    assert np.max(np.abs(same.transpose(0, 2, 1, 3) - orc.mqa_prefill(q.transpose(0, 2, 1, 3), Ks, Vs, lens))) <= 1e-14
+    # whole layer == the Section 2.3 batched listing with a causal mask
+    X = g.normal(size=(b, n, d))
+    P_q, P_k, P_v, P_o = (g.normal(size=(h, d, e)) for e in (k, k, v, v))
+    Q = np.einsum("bnd,hdk->bhnk", X, P_q)
+    Kc = np.einsum("bnd,hdk->bhnk", X, P_k)
+    Vc = np.einsum("bnd,hdv->bhnv", X, P_v)
+    Y = np.einsum("bhnv,hdv->bnd", orc.mha_prefill(Q, Kc, Vc, [n, n]), P_o)
+    ref = orc.multihead_attention_batched(X, X, orc.causal_mask(b, h, n), P_q, P_k, P_v, P_o)
+    assert np.max(np.abs(Y - ref)) <= 1e-12
+
+
 # ---------------------------------------------------------------- beam search (Section 4.1, Table 2 last column)
 def _beam_case(seed, b=3, beam=4, h=2, cap_s=7, cap_t=5, k=3, v=4):
     g = _rng(seed)
