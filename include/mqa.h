@@ -168,6 +168,15 @@ int mqa_append_kv_rows(void* K, void* V, const float* k_new, const float* v_new,
 int mqa_prefill_attention(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
                           int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
                           void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * The multi-head twin (Section 2.3 listing `MultiheadAttentionBatched` with its causal mask):
+ * q [b,h,n,k] and o [b,h,n,v] (head-major, so that the n queries of a head are adjacent rows),
+ * K [b,h,cap,k], V [b,h,cap,v]; query j of head t of sequence i attends to positions
+ * 0..lens[i]-n+j of K[i,t], V[i,t].  Same restrictions as mqa_prefill_attention.
+ */
+int mha_prefill_attention(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                          int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Beam search (the paper decodes with beam 4 in Section 4.1 and times it in Table 2): the

@@ -2,7 +2,7 @@
 (include/mqa.h) and a thin ctypes binding with the same names."""
 from .binding import (  # noqa: F401
     MQA_BF16, MQA_F32, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O, MQA_PROJ_Q, MqaError,
-    load_library, mha_decode_step, mha_decode_step_window, mqa_decode_step_window, mha_decode_workspace_bytes, mqa_append_kv, mqa_append_kv_rows, mqa_prefill_attention, mqa_decode_combine,
+    load_library, mha_decode_step, mha_decode_step_window, mqa_decode_step_window, mha_decode_workspace_bytes, mqa_append_kv, mqa_append_kv_rows, mqa_prefill_attention, mha_prefill_attention, mqa_decode_combine,
     mqa_decode_step_beams, mqa_decode_beams_workspace_bytes, mqa_beam_reorder_kv,
     mqa_decode_num_splits, mqa_decode_partials, mqa_decode_step, mqa_decode_workspace_bytes,
     mqa_project_qkvo, mqa_project_append_qkv, mqa_stack_add, mqa_stack_argmax, mqa_stack_embed, mqa_stack_layernorm, mqa_stack_relu,

@@ -17,7 +17,7 @@ MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
 
 EXPORTS = [
     "mqa_project_qkvo", "mqa_project_append_qkv", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
-    "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention",
+    "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mha_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
@@ -60,6 +60,7 @@ def load_library(path: str = LIB_PATH):
     lib.mha_decode_step_window.argtypes = win
     lib.mqa_append_kv_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
     lib.mqa_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    lib.mha_prefill_attention.argtypes = lib.mqa_prefill_attention.argtypes
     lib.mqa_decode_step_beams.argtypes = [vp] * 8 + [ci] * 8 + [cf, vp, sz, vp]
     lib.mqa_decode_beams_workspace_bytes.argtypes = [ci] * 8
     lib.mqa_decode_beams_workspace_bytes.restype = sz
@@ -272,6 +273,26 @@ def mqa_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stre
                                    workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != 0:
         raise MqaError("mqa_prefill_attention", rc)
+    return o
+
+
+def mha_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=None):
+    """q [b,h,n,k], K [b,h,cap,k], V [b,h,cap,v] bf16, lens [b] (after the append) -> o [b,h,n,v]."""
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
+    b, h, n, k = q.shape
+    cap, v = V.shape[-2], V.shape[-1]
+    if tuple(K.shape) != (b, h, cap, k) or tuple(V.shape) != (b, h, cap, v) or lens.numel() != b:
+        raise ValueError("shape mismatch in mha_prefill_attention")
+    if o is None:
+        o = torch.empty((b, h, n, v), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _default_workspace(q.device, mha_decode_workspace_bytes(b, n * h, cap, v))
+    rc = lib.mha_prefill_attention(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, n, h, cap, k, v,
+                                   _cache_dtype(K), float(scale), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise MqaError("mha_prefill_attention", rc)
     return o
 
 

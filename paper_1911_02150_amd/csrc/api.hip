@@ -101,11 +101,12 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
                 bool multi_head, int phase, int window = 0, int causal_n = 0) {
   if (window < 0 || causal_n < 0) return MQA_ERR_SHAPE;
   const int h_true = h;
-  if (causal_n > 0) {          // n queries x h heads per sequence are n*h rows sharing the sequence's K/V
-    if (multi_head || (long long)h * causal_n > (1 << 20)) return MQA_ERR_SHAPE;
-    h = h * causal_n;
-  }
-  int rc = check_decode_args(q, K, V, lens, o, b, h, cap, k, v, dt, (phase & 1) != 0);
+  if (causal_n > 0 && (long long)h * causal_n > (1 << 20)) return MQA_ERR_SHAPE;
+  // n queries x h heads per sequence: multi-query, n*h rows sharing the sequence's K/V;
+  // multi-head, b*h groups of n rows (the n queries of one head) over that head's K/V
+  if (causal_n > 0 && !multi_head) h = h * causal_n;
+  int rc = check_decode_args(q, K, V, lens, o, b, multi_head && causal_n > 0 ? h * causal_n : h, cap, k, v, dt,
+                             (phase & 1) != 0);
   if (rc) return rc;
   Tuning tn;
   if (tuning) {
@@ -114,7 +115,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
     tn.flags = tuning->flags;
   }
   const int nseq = multi_head ? b * h : b;
-  const int G = multi_head ? 1 : h;
+  const int G = multi_head ? (causal_n > 0 ? causal_n : 1) : h;
   Plan pl;
   if (causal_n > 0) tn.splits = 1;     // rows end at different positions: one range per workgroup, no merge pass
   rc = plan_decode(nseq, G, cap, window, k, v, dt == MQA_BF16, tn, &pl);
@@ -127,7 +128,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   DecodeParams p;
   p.q = q; p.K = K; p.V = V; p.lens = lens; p.o = o;
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
-  p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? h_true : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
+  p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? (multi_head ? 1 : h_true) : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
   p.qscale = scale * kLog2e;
   set_partials(&p, workspace, (long long)nseq * G, pl.S > 1 ? pl.S : 0, 0);
   // Ragged batches with several workgroups per compute unit: schedule the longest groups first
@@ -306,6 +307,14 @@ int mqa_prefill_attention(const float* q, const void* K, const void* V, const in
   if (n <= 0 || n > cap) return MQA_ERR_SHAPE;
   return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
                      nullptr, false, 3, 0, n);
+}
+
+int mha_prefill_attention(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                          int b, int n, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (n <= 0 || n > cap) return MQA_ERR_SHAPE;
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, true, 3, 0, n);
 }
 
 int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, const int32_t* lens_src,

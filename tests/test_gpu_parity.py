@@ -459,6 +459,23 @@ def test_prefill_attention(m, b, n, h, prefix):
     assert float((step - o[:, j]).abs().max()) <= 1e-4
 
 
+@pytest.mark.parametrize("b,n,h,prefix", [(2, 5, 8, 0), (2, 50, 3, 21), (1, 128, 8, 0)])
+def test_mha_prefill_attention(m, b, n, h, prefix):
+    cap = prefix + n + 5
+    g = mi.rng(4200 + n, b)
+    q = g.standard_normal((b, h, n, 128), dtype=np.float32) / np.float32(np.sqrt(128)) * np.float32(3)
+    c = mi.random_case(80 + n, b, h, cap, 128, 128, cache="bf16", lens=[prefix + n] * b, multi_head=True)
+    K, V = to_dev_cache(c["K"]), to_dev_cache(c["V"])
+    lens = torch.from_numpy(c["lens"]).to(DEV)
+    o = m.mha_prefill_attention(torch.from_numpy(q).to(DEV), K, V, lens)
+    ref = orc.mha_prefill(q, mi.cache_as_f64(c["K"]), mi.cache_as_f64(c["V"]), c["lens"])
+    check(o, ref, "bf16", f"mha prefill b={b} n={n} h={h} prefix={prefix}")
+    j = n // 2                                          # the same rows through a single-token multi-head step
+    step = m.mha_decode_step(torch.from_numpy(np.ascontiguousarray(q[:, :, j])).to(DEV), K, V,
+                             torch.full((b,), prefix + j + 1, dtype=torch.int32, device=DEV))
+    assert float((step - o[:, :, j]).abs().max()) <= 1e-4
+
+
 def test_prefill_prompt_then_decode(m):
     """A prompt written with one bulk append and attended in one call, then a decode step on top:
     the cache and lengths the prefill leaves are what the incremental path continues from."""
