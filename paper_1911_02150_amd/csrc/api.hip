@@ -348,10 +348,20 @@ int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, 
 #ifdef MQA_TIMELINE
   ps.timeline = po.timeline = nullptr;
 #endif
-  hipError_t e = bp.src.use_mfma ? launch_decode_mfma(ps, 0, st) : launch_decode_generic(ps, dt == MQA_BF16, st);
-  if (e != hipSuccess) return MQA_ERR_LAUNCH;
-  e = bp.own.use_mfma ? launch_decode_mfma(po, 0, st) : launch_decode_generic(po, dt == MQA_BF16, st);
-  if (e != hipSuccess) return MQA_ERR_LAUNCH;
+  if (bp.src.use_mfma && bp.own.use_mfma) {
+    // one launch for both caches: 32 heads per workgroup in both segments
+    const int hg_src = (ps.G + 31) / 32, hg_own = (po.G + 31) / 32;
+    ps.HG = hg_src;
+    ps.seg1 = po.seg0();
+    ps.seg1.HG = hg_own;
+    if (launch_decode_mfma_two(ps, (long long)ps.nseq * ps.S * hg_src, (long long)po.nseq * po.S * hg_own, st) != hipSuccess)
+      return MQA_ERR_LAUNCH;
+  } else {
+    hipError_t e = bp.src.use_mfma ? launch_decode_mfma(ps, 0, st) : launch_decode_generic(ps, dt == MQA_BF16, st);
+    if (e != hipSuccess) return MQA_ERR_LAUNCH;
+    e = bp.own.use_mfma ? launch_decode_mfma(po, 0, st) : launch_decode_generic(po, dt == MQA_BF16, st);
+    if (e != hipSuccess) return MQA_ERR_LAUNCH;
+  }
   CombineParams c;
   c.part_o = ps.part_o; c.part_m = ps.part_m; c.part_l = ps.part_l; c.o = o;
   c.rows = rows; c.v = v; c.PS = bp.slots; c.nseg = 2;

@@ -13,6 +13,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 // One decode launch.  "Sequences" here are KV groups: a multi-query call has
 // nseq = b groups of G = h heads; a multi-head call has nseq = b*h groups of
 // G = 1 head, and lens is indexed by seq / lens_div (lens_div = h).
+// What differs between the two caches of a two-segment launch (see DecodeParams).
+struct DecodeSegment {
+  const void* K;
+  const void* V;
+  const int32_t* lens;
+  int G, cap, chunk, S, HG, slot0, lens_div;
+};
+
 struct DecodeParams {
   const float* q;        // [nseq, G, k]
   const void* K;         // [nseq, cap, k]
@@ -36,6 +44,11 @@ struct DecodeParams {
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
   int merge_alias;       // MFMA kernel: 1 = the wave-merge buffers re-use the q operands' LDS
   float qscale;          // scale * log2(e): logits are kept in the log2 domain
+  // MFMA kernel, two-segment launches only: workgroups [nblocks0, grid) work on seg1 instead of
+  // the fields above (same q, o and partial-state rows)
+  int nblocks0;
+  DecodeSegment seg1;
+  __host__ __device__ DecodeSegment seg0() const { return DecodeSegment{K, V, lens, G, cap, chunk, S, HG, slot0, lens_div}; }
 #ifdef MQA_TIMELINE
   long long* timeline;   // debug builds only: [waves][8] wall-clock stamps
 #endif
@@ -69,6 +82,8 @@ struct Tuning {
 bool mfma_shape_ok(int G, int k, int v, int is_bf16);
 int mfma_heads_per_block(int G);
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
+// both segments in one launch (p.seg1 filled in, 32 heads per workgroup in both); p.order must be null
+hipError_t launch_decode_mfma_two(const DecodeParams& p, long long nblocks0, long long nblocks1, hipStream_t st);
 
 // decode_generic.hip: any k, v <= 256, float32 or bf16 cache.
 hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t st);

@@ -96,7 +96,10 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
 #define MQA_STAMP(i) do { } while (0)
 #endif
 
-template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL>
+// TWO_SEG: one launch covers two caches over the same q and output rows (beam search: the rows
+// shared by the hypotheses of a source, then each hypothesis' own rows); workgroups from
+// p.nblocks0 on take the second segment's cache, grouping and slots.
+template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false>
 __global__ __launch_bounds__(NW * 64, 2)
 void decode_mfma_kernel(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -106,31 +109,41 @@ void decode_mfma_kernel(DecodeParams p) {
   constexpr int NH = 16 * HB;                 // heads handled by this block
 
   // workgroup -> (sequence, range, head group); consecutive work items share an XCD
-  const int nb = gridDim.x, bid = blockIdx.x;
+  int nb = gridDim.x, bid = blockIdx.x;
+  DecodeSegment sg = p.seg0();
+  if constexpr (TWO_SEG) {
+    if (bid >= p.nblocks0) {
+      sg = p.seg1;
+      bid -= p.nblocks0;
+      nb -= p.nblocks0;
+    } else {
+      nb = p.nblocks0;
+    }
+  }
   int hg, srange, seq;
   if (p.order) {
     // Longest-first schedule: workgroups are dispatched in index order, round-robin over the
     // 8 XCDs, so XCD x takes the sequences ranked x, x+8, ... by length, longest first, and all
     // work items of a sequence stay on that XCD.
-    const int j = bid >> 3, items = p.S * p.HG;
+    const int j = bid >> 3, items = sg.S * sg.HG;
     const int t = (j / items) * 8 + (bid & 7);
     if (t >= p.nseq) return;                   // padding of the grid to a multiple of 8 sequences
-    hg = j % p.HG;
-    srange = (j / p.HG) % p.S;
+    hg = j % sg.HG;
+    srange = (j / sg.HG) % sg.S;
     seq = p.order[t];
   } else {
     const int wid = ((nb & 7) == 0) ? (bid & 7) * (nb >> 3) + (bid >> 3) : bid;
-    hg = wid % p.HG;
-    srange = (wid / p.HG) % p.S;
-    seq = wid / (p.HG * p.S);
+    hg = wid % sg.HG;
+    srange = (wid / sg.HG) % sg.S;
+    seq = wid / (sg.HG * sg.S);
   }
   const int head0 = hg * NH;
-  int begin = srange * p.chunk;                // < cap by construction of S and chunk; moved up below for a window
+  int begin = srange * sg.chunk;                // < cap by construction of S and chunk; moved up below for a window
 
-  const u32x4* Kbase = reinterpret_cast<const u32x4*>(p.K) + (size_t)seq * p.cap * kRowU4;
-  const u32x4* Vbase = reinterpret_cast<const u32x4*>(p.V) + (size_t)seq * p.cap * kRowU4;
+  const u32x4* Kbase = reinterpret_cast<const u32x4*>(sg.K) + (size_t)seq * sg.cap * kRowU4;
+  const u32x4* Vbase = reinterpret_cast<const u32x4*>(sg.V) + (size_t)seq * sg.cap * kRowU4;
   const int krow_in_tile = 4 * (i16 & 3) + (i16 >> 2);
-  const int rmax = p.cap - 1;
+  const int rmax = sg.cap - 1;
 
   // A tile past the end of the range is "fetched" from one fixed in-bounds address by all
   // lanes (a single cached line), so the prefetch needs no branch and costs no bandwidth.
@@ -168,8 +181,8 @@ void decode_mfma_kernel(DecodeParams p) {
     const int idx = tid + it * NT;
     const int hl = idx >> 4, c = idx & 15;               // head in block, 8-float chunk of the row
     qa[it] = qb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (idx < NH * 16 && head0 + hl < p.G) {
-      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * p.G + head0 + hl) * kD + c * 8);
+    if (idx < NH * 16 && head0 + hl < sg.G) {
+      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * sg.G + head0 + hl) * kD + c * 8);
       qa[it] = src[0];
       qb[it] = src[1];
     }
@@ -186,8 +199,8 @@ void decode_mfma_kernel(DecodeParams p) {
     load_v(tb, wave, real);
   }
   MQA_STAMP(1);
-  int L = p.lens[seq / p.lens_div];
-  L = L < 0 ? 0 : (L > p.cap ? p.cap : L);
+  int L = sg.lens[seq / sg.lens_div];
+  L = L < 0 ? 0 : (L > sg.cap ? sg.cap : L);
   // Local attention (the paper's Section 4.1 variant): only positions [lo, L) count; the ranges
   // then start at the 32-aligned position below lo, which is known only now.
   const int lo = window_lo(L, p.window);
@@ -200,26 +213,26 @@ void decode_mfma_kernel(DecodeParams p) {
   // Causal rows (prefill of n queries per sequence): row r = query r / h, at position L - n + r / h,
   // attends to positions <= its own.  `end` is the largest such limit in this workgroup.
   const int causal_h = p.causal_h;
-  const int nq = causal_h > 0 ? p.G / causal_h : 1;
+  const int nq = causal_h > 0 ? sg.G / causal_h : 1;
   int lim[HB];                                   // first position the lane's row (per head block) must NOT see
   int lim_min = L, lim_max = L;
   if (causal_h > 0) {
 #pragma unroll
-    for (int hb = 0; hb < HB; ++hb) lim[hb] = max(0, L - nq + min(head0 + 16 * hb + i16, p.G - 1) / causal_h + 1);
+    for (int hb = 0; hb < HB; ++hb) lim[hb] = max(0, L - nq + min(head0 + 16 * hb + i16, sg.G - 1) / causal_h + 1);
     lim_min = max(0, L - nq + head0 / causal_h + 1);
-    lim_max = max(0, L - nq + (min(head0 + NH, p.G) - 1) / causal_h + 1);
+    lim_max = max(0, L - nq + (min(head0 + NH, sg.G) - 1) / causal_h + 1);
   } else {
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) lim[hb] = L;
   }
-  const int end = min(begin + p.chunk, lim_max);
+  const int end = min(begin + sg.chunk, lim_max);
   const int mask_from = min(end, lim_min);        // tiles reaching beyond this position need masking
   if (end <= begin) {
     if (p.PS == 0) {          // empty sequence: zero output rows
       for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
         int hl = idx / (kD / 4), c4 = idx % (kD / 4);
-        if (head0 + hl < p.G)
-          reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head0 + hl) * kD)[c4] =
+        if (head0 + hl < sg.G)
+          reinterpret_cast<float4*>(p.o + ((size_t)seq * sg.G + head0 + hl) * kD)[c4] =
               make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
@@ -409,7 +422,7 @@ void decode_mfma_kernel(DecodeParams p) {
   for (int it = 0; it < ITERS; ++it) {
     const int idx = tid + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
-    if (head0 + hl >= p.G) continue;
+    if (head0 + hl >= sg.G) continue;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) M = fmaxf(M, fw[it][w]);
@@ -426,9 +439,9 @@ void decode_mfma_kernel(DecodeParams p) {
     if (p.PS == 0) {
       const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;      // (a causal row with nothing to see: zeros)
       a.x *= inv; a.y *= inv; a.z *= inv; a.w *= inv;
-      reinterpret_cast<float4*>(p.o + ((size_t)seq * p.G + head) * kD)[c4] = a;
+      reinterpret_cast<float4*>(p.o + ((size_t)seq * sg.G + head) * kD)[c4] = a;
     } else {
-      const size_t pidx = ((size_t)seq * p.G + head) * p.PS + p.slot0 + srange;
+      const size_t pidx = ((size_t)seq * sg.G + head) * p.PS + sg.slot0 + srange;
       reinterpret_cast<float4*>(p.part_o + pidx * kD)[c4] = a;
       if (c4 == 0) {
         p.part_m[pidx] = M;
@@ -483,6 +496,34 @@ bool mfma_shape_ok(int G, int k, int v, int is_bf16) {
 }
 
 int mfma_heads_per_block(int G) { return G <= 16 ? 16 : 32; }
+
+hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, long long nblocks1, hipStream_t st) {
+  constexpr int HB = 2, NW = 4;
+  DecodeParams p = p_in;
+  p.nblocks0 = (int)nblocks0;
+  p.order = nullptr;
+  p.merge_alias = 1;                          // small LDS footprint: two workgroups per CU
+  const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
+  const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 5 * NW * 16 * HB) * sizeof(float);
+  const size_t lds = q_bytes > merge_bytes ? q_bytes : merge_bytes;        // 68.5 KiB
+  // non-temporal loads unless some head group is meant to find its tiles in L2
+  const bool ntl = p.HG == 1 && p.seg1.HG == 1;
+  void (*kern)(DecodeParams) = ntl ? decode_mfma_kernel<HB, NW, true, true, true, true>
+                                   : decode_mfma_kernel<HB, NW, true, true, false, true>;
+  {                                           // opt in to more than 64 KiB of LDS, once per device and variant
+    static bool done[64][2] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (!done[dev][ntl]) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      done[dev][ntl] = true;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(nblocks0 + nblocks1)), dim3(NW * 64), lds, st, p);
+  return hipGetLastError();
+}
 
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
   const bool wide = (flags & 16) != 0;       // 8 waves per workgroup instead of 4
