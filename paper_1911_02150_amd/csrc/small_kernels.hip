@@ -82,24 +82,50 @@ void length_order_kernel(const int32_t* lens, int lens_div, int nseq, int cap, i
   const int tid = threadIdx.x;
   count[tid] = 0;
   __syncthreads();
+  const float per_pos = 1023.0f / (float)cap;
   auto cls = [&](int i) {
     int L = lens[i / lens_div];
     L = L < 0 ? 0 : (L > cap ? cap : L);
-    return 1023 - (int)(((long long)L * 1023) / cap);       // class 0 holds the longest
+    return 1023 - min(1023, (int)((float)L * per_pos));      // class 0 holds the longest
   };
+  // all groups in one class (equal lengths, the common case): keep the given order and spare the
+  // atomics, which would all hit one counter
+  __shared__ int cmin[16], cmax[16];
+  int lo = 1023, hi = 0;
+  for (int i = tid; i < nseq; i += 1024) {
+    const int c = cls(i);
+    lo = min(lo, c);
+    hi = max(hi, c);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    lo = min(lo, __shfl_xor(lo, off));
+    hi = max(hi, __shfl_xor(hi, off));
+  }
+  if ((tid & 63) == 0) { cmin[tid >> 6] = lo; cmax[tid >> 6] = hi; }
+  __syncthreads();
+  for (int w = 0; w < 16; ++w) { lo = min(lo, cmin[w]); hi = max(hi, cmax[w]); }
+  if (lo >= hi) {
+    for (int i = tid; i < nseq; i += 1024) order[i] = i;
+    return;
+  }
   for (int i = tid; i < nseq; i += 1024) atomicAdd(&count[cls(i)], 1);
   __syncthreads();
-  // exclusive prefix sum over the classes
-  int x = count[tid];
-  start[tid] = x;
-  __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const int y = tid >= off ? start[tid - off] : 0;
-    __syncthreads();
-    start[tid] += y;
-    __syncthreads();
+  // exclusive prefix sum over the classes: inside each wave with shuffles, then over the 16 wave totals
+  __shared__ int wave_total[16];
+  const int lane = tid & 63, wave = tid >> 6;
+  const int x = count[tid];
+  int incl = x;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(incl, off);
+    if (lane >= off) incl += y;
   }
-  start[tid] -= x;
+  if (lane == 63) wave_total[wave] = incl;
+  __syncthreads();
+  int before = 0;                                  // classes in earlier waves
+  for (int w = 0; w < wave; ++w) before += wave_total[w];
+  start[tid] = before + incl - x;
   __syncthreads();
   for (int i = tid; i < nseq; i += 1024) order[atomicAdd(&start[cls(i)], 1)] = i;
 }

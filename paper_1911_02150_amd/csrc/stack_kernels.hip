@@ -55,30 +55,43 @@ void relu_kernel(float* __restrict__ a, size_t n) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) a[i] = fmaxf(a[i], 0.f);
 }
 
-// out[row] = index of the largest element of the row, the lowest index among equals
-__global__ __launch_bounds__(256)
+// out[row] = index of the largest element of the row, the lowest index among equals.  One
+// workgroup of 1024 threads per row, 16-byte loads (rows are 16-byte aligned when n % 4 == 0).
+__device__ __forceinline__ void take_better(float& best, int& bi, float v, int i) {
+  if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+}
+
+__global__ __launch_bounds__(1024)
 void argmax_kernel(const float* __restrict__ x, int32_t* __restrict__ out, int n) {
-  __shared__ float sv[256];
-  __shared__ int si[256];
+  __shared__ float sv[16];
+  __shared__ int si[16];
   const float* xr = x + (size_t)blockIdx.x * n;
+  const int tid = threadIdx.x;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < n; i += 256) {
-    const float v = xr[i];
-    if (v > best || (v == best && i < bi)) { best = v; bi = i; }
-  }
-  sv[threadIdx.x] = best;
-  si[threadIdx.x] = bi;
-  __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (threadIdx.x < s) {
-      const float v = sv[threadIdx.x + s];
-      const int j = si[threadIdx.x + s];
-      if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && j < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = j; }
+  if ((n & 3) == 0) {
+    const float4* x4 = reinterpret_cast<const float4*>(xr);
+    for (int i = tid; i < (n >> 2); i += 1024) {
+      const float4 v = x4[i];
+      take_better(best, bi, v.x, 4 * i);
+      take_better(best, bi, v.y, 4 * i + 1);
+      take_better(best, bi, v.z, 4 * i + 2);
+      take_better(best, bi, v.w, 4 * i + 3);
     }
-    __syncthreads();
+  } else {
+    for (int i = tid; i < n; i += 1024) take_better(best, bi, xr[i], i);
   }
-  if (threadIdx.x == 0) out[blockIdx.x] = si[0];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) take_better(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
+  if ((tid & 63) == 0) { sv[tid >> 6] = best; si[tid >> 6] = bi; }
+  __syncthreads();
+  if (tid < 64) {
+    best = tid < 16 ? sv[tid] : -INFINITY;
+    bi = tid < 16 ? si[tid] : 0x7fffffff;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) take_better(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
+    if (tid == 0) out[blockIdx.x] = bi;
+  }
 }
 
 }  // namespace
@@ -101,7 +114,7 @@ hipError_t launch_relu(float* a, size_t n, hipStream_t st) {
   return hipGetLastError();
 }
 hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStream_t st) {
-  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(256), 0, st, x, out, n);
+  hipLaunchKernelGGL(argmax_kernel, dim3(rows), dim3(1024), 0, st, x, out, n);
   return hipGetLastError();
 }
 
