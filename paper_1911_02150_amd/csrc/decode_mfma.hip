@@ -10,7 +10,9 @@
 //           More than 32 heads are split into head groups: the groups of one (sequence, range)
 //           are neighbouring work items on one XCD and read the same tiles at about the same
 //           time, so with cacheable loads the second read is served by L2.  (One wave holding
-//           64 heads spills, and two teams of waves in one workgroup measured slower.)
+//           64 heads needs 128 accumulator registers and a workgroup per CU and measured no
+//           faster; two teams of waves in one workgroup measured slower.)
+//           With an order array (ragged batches) the sequences are taken longest first.
 //   block = NW independent wavefronts; wave w takes the 32-position tiles
 //           w, w+NW, ... of the range, so the block streams its range front to back.
 //   Each wave keeps, for all 16*HB heads, a running maximum, a running sum and
