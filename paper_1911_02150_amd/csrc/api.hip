@@ -42,7 +42,7 @@ int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_b
   if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G) - 1) / mfma_heads_per_block(G);
   const int min_chunk = pl->use_mfma ? 128 : 256;
   int max_s = (cap + min_chunk - 1) / min_chunk;
-  if (max_s > kMaxSplits) max_s = kMaxSplits;
+  if (max_s > kMaxAutoSplits) max_s = kMaxAutoSplits;
   if (max_s < 1) max_s = 1;
   int S;
   if (tn.splits > 0) {
@@ -248,8 +248,12 @@ int mqa_decode_combine(const int32_t* lens, float* o, int b, int h, int cap, int
 
 size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v) {
   if (b <= 0 || h <= 0 || cap <= 0 || v <= 0) return 0;
+  // ranges: at most one per 32 positions; a caller may force up to kMaxSplits, the heuristics
+  // choose up to ceil(256 / groups) <= ceil(256 / b)
   int S = (cap + 31) / 32;
-  if (S > kMaxSplits) S = kMaxSplits;
+  int most = (kTargetBlocks + b - 1) / b;
+  if (most < kMaxSplits) most = kMaxSplits;
+  if (S > most) S = most;
   return partial_bytes((long long)b * h, S, v) + 16 + (size_t)b * sizeof(int32_t);   // + the schedule of the groups
 }
 

@@ -7,7 +7,8 @@
 
 namespace mqa {
 
-constexpr int kMaxSplits = 64;          // upper bound on position ranges per sequence
+constexpr int kMaxSplits = 64;          // upper bound on position ranges per sequence a caller can ask for
+constexpr int kMaxAutoSplits = 256;     // ... and that the heuristics choose (one sequence alone fills the chip)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // One decode launch.  "Sequences" here are KV groups: a multi-query call has

@@ -72,6 +72,80 @@ void combine_kernel(CombineParams p) {
   reinterpret_cast<float4*>(p.o + (size_t)row * p.v)[c4] = a;
 }
 
+// The same merge for many slots per row (a few long sequences spread over up to 256 ranges):
+// one workgroup per output row, thread = (4 columns, slot group sg); a thread folds the slots
+// sg, sg + SG, ... in batches of 8 loads, then the SG partial states are folded through LDS.
+__global__ __launch_bounds__(256)
+void combine_wide_kernel(CombineParams p) {
+  __shared__ float s_m[256], s_l[256];
+  __shared__ float4 s_a[256];
+  const int v4 = p.v >> 2, SG = 256 / v4;
+  const int tid = threadIdx.x;
+  const int c4 = tid % v4, sgrp = tid / v4;
+  const long long row = blockIdx.x;
+  const size_t base = (size_t)row * p.PS;
+  const int n0 = valid_ranges(p.seg[0], row);
+  const int s1 = p.seg[0].S;
+  const int n1 = p.nseg > 1 ? valid_ranges(p.seg[1], row) : 0;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  float M = -INFINITY, lsum = 0.f;
+  if (sgrp < SG) {
+    for (int sb = sgrp; sb < p.PS; sb += 8 * SG) {
+      float pm[8], pl[8];
+      float4 po[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const size_t pi = base + min(sb + j * SG, p.PS - 1);
+        pm[j] = p.part_m[pi];
+        pl[j] = p.part_l[pi];
+        po[j] = reinterpret_cast<const float4*>(p.part_o + pi * p.v)[c4];
+      }
+      float Mn = M;
+      bool ok[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int sl = sb + j * SG;
+        ok[j] = sl < p.PS && (sl < n0 || (sl >= s1 && sl < s1 + n1));
+        if (ok[j]) Mn = fmaxf(Mn, pm[j]);
+      }
+      if (Mn == -INFINITY) continue;
+      const float f0 = __builtin_amdgcn_exp2f(M - Mn);
+      a.x *= f0; a.y *= f0; a.z *= f0; a.w *= f0;
+      lsum *= f0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (ok[j]) {
+          const float f = __builtin_amdgcn_exp2f(pm[j] - Mn);
+          a.x += f * po[j].x; a.y += f * po[j].y; a.z += f * po[j].z; a.w += f * po[j].w;
+          lsum += f * pl[j];
+        }
+      M = Mn;
+    }
+  }
+  s_m[tid] = M;
+  s_l[tid] = lsum;
+  s_a[tid] = a;
+  __syncthreads();
+  if (sgrp == 0) {
+    float Mt = -INFINITY;
+    for (int g = 0; g < SG; ++g) Mt = fmaxf(Mt, s_m[g * v4 + c4]);
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lt = 0.f;
+    if (Mt != -INFINITY)
+      for (int g = 0; g < SG; ++g) {
+        const float f = __builtin_amdgcn_exp2f(s_m[g * v4 + c4] - Mt);     // 0 for a group that saw nothing
+        const float4 x = s_a[g * v4 + c4];
+        r.x += f * x.x; r.y += f * x.y; r.z += f * x.z; r.w += f * x.w;
+        lt += f * s_l[g * v4 + c4];
+      }
+    if (lt > 0.f) {
+      const float inv = 1.0f / lt;
+      r.x *= inv; r.y *= inv; r.z *= inv; r.w *= inv;
+    }
+    reinterpret_cast<float4*>(p.o + (size_t)row * p.v)[c4] = r;
+  }
+}
+
 // Scheduling aid for ragged batches: a permutation of the KV groups by decreasing length
 // (counting sort over 1024 length classes; the order inside a class is arbitrary, which only
 // affects which workgroup runs when, never a result).  One workgroup.
@@ -223,7 +297,8 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t st) {
   const size_t total = (size_t)p.rows * (p.v >> 2);
   const dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (p.PS <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, p);
-  else hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
+  else if (p.PS <= 16 || p.rows > (1 << 20)) hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, p);
+  else hipLaunchKernelGGL(combine_wide_kernel, dim3((unsigned)p.rows), block, 0, st, p);
   return hipGetLastError();
 }
 

@@ -42,6 +42,8 @@ def test_host_side_sizes_and_plan():
     assert m.mqa_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4 + 16 + 2 * 4
     assert m.mha_decode_workspace_bytes(2, 3, 40, 8) == 2 * 2 * 3 * 10 * 4 + 16 + 6 * 4
     assert m.mqa_decode_workspace_bytes(0, 3, 40, 8) == 0
+    assert m.mqa_decode_workspace_bytes(1, 32, 1 << 17, 128) == 256 * 32 * 130 * 4 + 16 + 4     # one sequence: up to 256 ranges
+    assert m.mqa_decode_num_splits(1, 32, 1 << 17, 128, 128, m.MQA_BF16) == 256
     assert m.mqa_decode_num_splits(128, 8, 128, 128, 128, m.MQA_BF16) == 1          # short caches: one range
     assert m.mqa_decode_num_splits(64, 32, 8192, 128, 128, m.MQA_BF16) > 1          # long cache: split
     assert m.mqa_decode_num_splits(64, 32, 8192, 128, 128, m.MQA_BF16, tuning=dict(splits=5)) == 5

@@ -72,6 +72,7 @@ MFMA_CASES = [
     (10, 2, 40, 64, "with_zero", 2),
     (11, 1, 8, 4096, "ragged", 64),        # the maximum number of ranges: the merge folds 8 batches of slots
     (12, 2, 32, 2500, "ragged", 20),
+    (13, 1, 32, 40000, "ragged", 0),       # one long sequence: the heuristics spread it over up to 256 ranges
 ]
 
 
