@@ -108,6 +108,10 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
 // gemm.hip: the same GEMM for large row counts / wide outputs (hipErrorNotSupported: too small, use launch_project's own kernel)
 hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* out,
                              int rows, int d, int h, int kv, hipStream_t st);
+hipError_t launch_gemm_tiled_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
+                                 float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
+                                 int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
+                                 hipStream_t st);
 hipError_t launch_project_qkv_append(const float* x, const float* P_q, const float* P_k, const float* P_v,
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,

@@ -217,6 +217,9 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
                                      hipStream_t st) {
+  const hipError_t big = launch_gemm_tiled_qkv(x, P_q, P_k, P_v, q, K, V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v,
+                                               is_bf16, st);
+  if (big != hipErrorNotSupported) return big;
   const int ntot = h * k + h_kv * (k + v);
   const long long tiles32 = (long long)(ntot / 32) * ((rows + 31) / 32);
   const bool t32 = tiles32 >= 512 && (k % 32) == 0 && (v % 32) == 0;

@@ -73,6 +73,7 @@ MFMA_CASES = [
     (11, 1, 8, 4096, "ragged", 64),        # the maximum number of ranges: the merge folds 8 batches of slots
     (12, 2, 32, 2500, "ragged", 20),
     (13, 1, 32, 40000, "ragged", 0),       # one long sequence: the heuristics spread it over up to 256 ranges
+    (14, 3, 8, 3000, "with_zero", 24),     # many slots per row with empty sequences and unwritten ranges
 ]
 
 
@@ -547,6 +548,9 @@ def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, spli
     (512, 256, 8, 128, 64, 9, "bf16", False),         # enough tiles for the 32x32 variant
     (5, 72, 3, 48, 16, 7, "f32", False),
     (33, 136, 4, 32, 32, 5, "f32", True),
+    (1024, 264, 8, 128, 128, 6, "bf16", False),       # large batch: the LDS-tiled kernel, 64x64 tiles
+    (2500, 264, 8, 128, 128, 4, "bf16", False),       # ... 128x128 tiles, ragged row edge
+    (1400, 136, 4, 64, 64, 5, "f32", True),           # ... multi-head rows
 ])
 def test_fused_qkv_projection_and_append(m, b, d, h, k, v, cap, cache, mh):
     g = mi.rng(3300, b + d)
@@ -589,4 +593,5 @@ def test_fused_qkv_projection_and_append(m, b, d, h, k, v, cap, cache, mh):
     assert torch.equal(l2, lens_out)
     ulp = 2.0 ** -7 if cache == "bf16" else 1e-5
     assert float((K2.float() - K.float()).abs().max()) <= ulp * float(K.float().abs().max())
-    assert float(((K2.float() - K.float()) != 0).float().mean()) < 1e-2
+    if cache == "bf16":       # float32 sums in another order rarely cross a bf16 rounding boundary
+        assert float(((K2.float() - K.float()) != 0).float().mean()) < 1e-2
