@@ -198,6 +198,18 @@ def other_workloads(m, mi, dev):
         name = "3_decoder_stack_" + ("mha" if mh else "mqa") + ("" if bsz == cfg["b"] else f"_b{bsz}")
         out[name] = {"step_us": t, "us_per_token": t / bsz, "tokens_per_s": bsz / (t * 1e-6), "b": bsz,
                      "cached_positions": cfg["cap"], "layers": cfg["layers"]}
+        if not mh and bsz == cfg["b"]:
+            # the 128-token prompts of the same workload in one prefill pass (bulk append + causal attention per layer)
+            prompts = torch.randint(0, cfg["vocab"], (bsz, cfg["prompt"]), dtype=torch.int32, device=dev)
+
+            def prefill(i):
+                for l in range(cfg["layers"]):
+                    st_.lens[l].zero_()
+                st_.prefill(prompts)
+            ms = time_region(prefill, 3, 1, settle_s=0.0)
+            ntok = bsz * cfg["prompt"]
+            out["3_decoder_stack_mqa_prefill"] = {"prompt_ms": ms, "us_per_token": ms * 1e3 / ntok,
+                                                  "tokens_per_s": ntok / (ms * 1e-3), "b": bsz, "prompt": cfg["prompt"]}
         del st_, w
     # beam-4 decoding: (a) workload 2's shape, 128 sources, 128 shared + 128 own positions per hypothesis;
     # (b) long prompts, 16 sources, 8192 shared + 128 own.  Against the same step over per-hypothesis copies of
