@@ -58,6 +58,7 @@ BEAM_CASES = [
     (8, 2, 4, 8, 100, 20, 128, 128, "bf16", "ragged", [0] * 8),        # first step: nothing generated yet
     (9, 2, 4, 8, 100, 20, 128, 128, "bf16", [0, 0], "full"),           # no shared rows at all
     (10, 2, 2, 8, 100, 20, 128, 128, "bf16", [0, 37], [0, 5, 0, 0]),   # a hypothesis with nothing to see: zeros
+    (11, 2, 2, 40, 200, 40, 128, 128, "bf16", "ragged", "ragged"),     # more than 32 heads: head groups in both parts
 ]
 
 

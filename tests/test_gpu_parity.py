@@ -74,6 +74,8 @@ MFMA_CASES = [
     (12, 2, 32, 2500, "ragged", 20),
     (13, 1, 32, 40000, "ragged", 0),       # one long sequence: the heuristics spread it over up to 256 ranges
     (14, 3, 8, 3000, "with_zero", 24),     # many slots per row with empty sequences and unwritten ranges
+    (15, 4, 8, 1, "full", 0),              # a cache of one position: the output is that V row
+    (16, 2, 8, 7, [7, 3], 0),
 ]
 
 
