@@ -125,7 +125,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
     if (!workspace || workspace_bytes < partial_bytes((long long)nseq * G, pl.S, v)) return MQA_ERR_WORKSPACE;
     if (misaligned(workspace)) return MQA_ERR_ALIGN;
   }
-  DecodeParams p;
+  DecodeParams p = {};
   p.q = q; p.K = K; p.V = V; p.lens = lens; p.o = o;
   p.nseq = nseq; p.G = G; p.cap = cap; p.lens_div = multi_head ? h : 1;
   p.k = k; p.v = v; p.window = window; p.causal_h = causal_n > 0 ? (multi_head ? 1 : h_true) : 0; p.chunk = pl.chunk; p.S = pl.S; p.HG = pl.HG;
@@ -163,9 +163,10 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   return MQA_OK;
 }
 
-// Beam search step: the hypotheses of a source attend to the source's shared rows (one launch,
-// beam*h rows per K/V group) and to their own rows (a second launch, h rows per group); the two
-// launches leave partial states in disjoint slots of the same rows and one merge pass finishes.
+// Beam search step: the hypotheses of a source attend to the source's shared rows (beam*h rows per
+// K/V group) and to their own rows (h rows per group); the two parts leave partial states in
+// disjoint slots of the same rows (one launch for both when the MFMA kernel serves both, else
+// two) and one merge pass finishes.
 struct BeamPlan {
   Plan src, own;
   int slots;
@@ -336,7 +337,7 @@ int mqa_decode_step_beams(const float* q, const void* K_src, const void* V_src, 
   if (!workspace || workspace_bytes < partial_bytes(rows, bp.slots, v)) return MQA_ERR_WORKSPACE;
   if (misaligned(workspace)) return MQA_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  DecodeParams ps;
+  DecodeParams ps = {};
   ps.q = q; ps.K = K_src; ps.V = V_src; ps.lens = lens_src; ps.o = o;
   ps.nseq = b; ps.G = beam * h; ps.cap = cap_src; ps.lens_div = 1;
   ps.order = nullptr;
