@@ -83,6 +83,16 @@ int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float*
                      int rows, int d, int h, int kv, void* stream);
 
 /*
+ * The same projections with an epilogue applied to every output element before it is stored,
+ * for callers that chain them (a decoder layer's residual stream and feed-forward block):
+ * MQA_EPI_STORE as above; MQA_EPI_RELU stores max(x, 0); MQA_EPI_ADD adds x to what `out`
+ * already holds (the residual connection around the attention of Section 4.1's layers).
+ */
+typedef enum { MQA_EPI_STORE = 0, MQA_EPI_RELU = 1, MQA_EPI_ADD = 2 } mqa_proj_epilogue;
+int mqa_project_qkvo_ex(mqa_proj_mode mode, const float* in, const float* P, float* out,
+                        int rows, int d, int h, int kv, mqa_proj_epilogue epilogue, void* stream);
+
+/*
  * The first three lines of the incremental listings plus the concat, in one launch: q = x . P_q
  * is written to q [b,h,k]; the new rows x . P_k, x . P_v go straight into row lens_in[i] of the
  * caches (rounded as in mqa_append_kv) and lens_out[i] = lens_in[i] + 1.  Same results as

@@ -14,9 +14,10 @@ LIB_PATH = os.path.join(_PKG_DIR, "libmqa_decode.so")
 
 MQA_F32, MQA_BF16 = 0, 1
 MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
+MQA_EPI_STORE, MQA_EPI_RELU, MQA_EPI_ADD = 0, 1, 2
 
 EXPORTS = [
-    "mqa_project_qkvo", "mqa_project_append_qkv", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
+    "mqa_project_qkvo", "mqa_project_qkvo_ex", "mqa_project_append_qkv", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
     "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mha_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
@@ -51,6 +52,7 @@ def load_library(path: str = LIB_PATH):
     tp = ctypes.POINTER(mqa_tuning)
     dec = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
     lib.mqa_project_qkvo.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, vp]
+    lib.mqa_project_qkvo_ex.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, vp]
     lib.mqa_project_append_qkv.argtypes = [vp] * 9 + [ci] * 8 + [vp]
     lib.mqa_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
     lib.mqa_decode_step.argtypes = dec
@@ -375,9 +377,7 @@ def mqa_beam_reorder_kv(K_src, V_src, lens_src, parent, K_dst, V_dst, lens_dst, 
         raise MqaError("mqa_beam_reorder_kv", rc)
 
 
-def mqa_project_qkvo(mode, x, P, out=None, stream=None):
-    """mode Q/KV_MH: x [rows,d], P [h,d,kv] -> [rows,h,kv];  KV: P [d,kv] -> [rows,kv];
-    O: x [rows,h,kv], P [h,d,kv] -> [rows,d]."""
+def _project(fn_name, mode, x, P, out, epilogue, stream):
     lib = load_library()
     _check(x, "in", torch.float32), _check(P, "P", torch.float32)
     rows = x.shape[0]
@@ -398,12 +398,30 @@ def mqa_project_qkvo(mode, x, P, out=None, stream=None):
     if not ok:
         raise ValueError(f"shape mismatch: in {tuple(x.shape)} P {tuple(P.shape)} mode {mode}")
     if out is None:
+        if epilogue == MQA_EPI_ADD:
+            raise ValueError("MQA_EPI_ADD accumulates into `out`: pass it")
         out = torch.empty(oshape, dtype=torch.float32, device=x.device)
     _check(out, "out", torch.float32)
-    rc = lib.mqa_project_qkvo(mode, _ptr(x), _ptr(P), _ptr(out), rows, d, h, kv, _stream(stream))
+    if out.numel() != rows * (oshape[1] if len(oshape) == 2 else oshape[1] * oshape[2]):
+        raise ValueError("out has the wrong size")
+    if epilogue is None:
+        rc = lib.mqa_project_qkvo(mode, _ptr(x), _ptr(P), _ptr(out), rows, d, h, kv, _stream(stream))
+    else:
+        rc = lib.mqa_project_qkvo_ex(mode, _ptr(x), _ptr(P), _ptr(out), rows, d, h, kv, int(epilogue), _stream(stream))
     if rc != 0:
-        raise MqaError("mqa_project_qkvo", rc)
+        raise MqaError(fn_name, rc)
     return out
+
+
+def mqa_project_qkvo(mode, x, P, out=None, stream=None):
+    """mode Q/KV_MH: x [rows,d], P [h,d,kv] -> [rows,h,kv];  KV: P [d,kv] -> [rows,kv];
+    O: x [rows,h,kv], P [h,d,kv] -> [rows,d]."""
+    return _project("mqa_project_qkvo", mode, x, P, out, None, stream)
+
+
+def mqa_project_qkvo_ex(mode, x, P, out=None, epilogue=MQA_EPI_STORE, stream=None):
+    """As mqa_project_qkvo with an epilogue: MQA_EPI_RELU stores max(x, 0), MQA_EPI_ADD adds to `out`."""
+    return _project("mqa_project_qkvo_ex", mode, x, P, out, epilogue, stream)
 
 
 def mqa_stream_read(src, sink, stream=None):

@@ -186,6 +186,20 @@ int plan_beams(int b, int beam, int h, int cap_src, int cap_own, int k, int v, i
   return MQA_OK;
 }
 
+// the four projections, with what happens to a finished output element (0 store, 1 relu, 2 add to out)
+int project_impl(int mode, const float* in, const float* P, float* out, int rows, int d, int h, int kv, int epilogue,
+                 void* stream) {
+  if (!in || !P || !out) return MQA_ERR_NULL;
+  if (mode < 0 || mode > 3 || epilogue < 0 || epilogue > 2) return MQA_ERR_DTYPE;
+  if (mode == MQA_PROJ_KV) h = 1;
+  if (rows <= 0 || d <= 0 || h <= 0 || kv <= 0) return MQA_ERR_SHAPE;
+  if ((d & 7) || (kv & 7)) return MQA_ERR_SHAPE;
+  if (misaligned(in) || misaligned(P) || misaligned(out)) return MQA_ERR_ALIGN;
+  if (launch_project(mode, in, P, out, rows, d, h, kv, epilogue, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -404,15 +418,12 @@ int mqa_beam_reorder_kv(const void* K_src, const void* V_src, const int32_t* len
 
 int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,
                      int rows, int d, int h, int kv, void* stream) {
-  if (!in || !P || !out) return MQA_ERR_NULL;
-  if ((int)mode < 0 || (int)mode > 3) return MQA_ERR_DTYPE;
-  if (mode == MQA_PROJ_KV) h = 1;
-  if (rows <= 0 || d <= 0 || h <= 0 || kv <= 0) return MQA_ERR_SHAPE;
-  if ((d & 7) || (kv & 7)) return MQA_ERR_SHAPE;
-  if (misaligned(in) || misaligned(P) || misaligned(out)) return MQA_ERR_ALIGN;
-  if (launch_project((int)mode, in, P, out, rows, d, h, kv, static_cast<hipStream_t>(stream)) != hipSuccess)
-    return MQA_ERR_LAUNCH;
-  return MQA_OK;
+  return project_impl((int)mode, in, P, out, rows, d, h, kv, 0, stream);
+}
+
+int mqa_project_qkvo_ex(mqa_proj_mode mode, const float* in, const float* P, float* out,
+                        int rows, int d, int h, int kv, mqa_proj_epilogue epilogue, void* stream) {
+  return project_impl((int)mode, in, P, out, rows, d, h, kv, (int)epilogue, stream);
 }
 
 int mqa_project_append_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,

@@ -102,12 +102,13 @@ hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStr
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 // project.hip
+// epilogue: 0 store, 1 store max(x, 0), 2 add to what out holds
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
-                          int rows, int d, int h, int kv, hipStream_t st);
+                          int rows, int d, int h, int kv, int epilogue, hipStream_t st);
 
 // gemm.hip: the same GEMM for large row counts / wide outputs (hipErrorNotSupported: too small, use launch_project's own kernel)
 hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* out,
-                             int rows, int d, int h, int kv, hipStream_t st);
+                             int rows, int d, int h, int kv, int epilogue, hipStream_t st);
 hipError_t launch_gemm_tiled_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
                                  float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                  int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
@@ -129,6 +130,13 @@ hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStrea
 // First position a sequence of length L attends to, and the 32-aligned position its ranges start from.
 __device__ __forceinline__ int window_lo(int L, int window) { return window > 0 ? max(0, L - window) : 0; }
 __device__ __forceinline__ int window_base(int L, int window) { return window_lo(L, window) & ~31; }
+
+// what a GEMM does with a finished output element (see launch_project)
+__device__ __forceinline__ float apply_epilogue(float x, const float* dst, int epilogue) {
+  if (epilogue == 1) return fmaxf(x, 0.f);
+  if (epilogue == 2) return x + *dst;
+  return x;
+}
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);

@@ -47,8 +47,8 @@ struct QkvAppend {
 // B_KCONTIG = true : B[c][n] = P[(c / kv) * d * kv + n * kv + c % kv]   (C = h * kv, N = d)
 template <bool B_KCONTIG, int BM, int BN, bool QKV = false>
 __global__ __launch_bounds__(256)
-void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P_in, float* __restrict__ out,
-                       int rows, int d, int h_in, int kv_in, QkvAppend f) {
+void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P_in, float* out,
+                       int rows, int d, int h_in, int kv_in, int epilogue, QkvAppend f) {
   constexpr int RB = BM / 64, CB = BN / 64;            // 32x32 blocks per wave in each direction
   constexpr int A_F4 = BM * BK / 4 / 256;              // float4 loads per thread per K-step
   constexpr int B_F4 = BN * BK / 4 / 256;
@@ -183,7 +183,8 @@ void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P
         const int row = row0 + wrow + 32 * r + 8 * (e >> 2) + 4 * kk + (e & 3);
         if (row >= rows || n >= N) continue;
         if (!QKV || which == 0) {
-          out[(size_t)row * N + n] = acc[r][c][e];
+          float* dst = out + (size_t)row * N + n;
+          *dst = apply_epilogue(acc[r][c][e], dst, epilogue);
         } else {
           const int L = f.lens_in[row];
           if (L < 0 || L >= f.cap) continue;                       // at capacity: the cache is left as it is
@@ -204,7 +205,7 @@ void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P
 
 template <bool KC, int BM, int BN, bool QKV = false>
 hipError_t launch_tiled(const float* in, const float* P, float* out, int rows, int d, int h, int kv, int N,
-                        hipStream_t st, const QkvAppend& f = QkvAppend{}) {
+                        int epilogue, hipStream_t st, const QkvAppend& f = QkvAppend{}) {
   constexpr size_t lds = 2 * (size_t)(BM * kAPitch + b_tile_floats<BN>(KC)) * sizeof(float);
   auto kern = gemm_tiled_kernel<KC, BM, BN, QKV>;
   if (lds > 64 * 1024) {
@@ -219,7 +220,7 @@ hipError_t launch_tiled(const float* in, const float* P, float* out, int rows, i
     }
   }
   const dim3 grid((N + BN - 1) / BN, (rows + BM - 1) / BM), block(256);
-  hipLaunchKernelGGL(kern, grid, block, lds, st, in, P, out, rows, d, h, kv, f);
+  hipLaunchKernelGGL(kern, grid, block, lds, st, in, P, out, rows, d, h, kv, epilogue, f);
   return hipGetLastError();
 }
 
@@ -228,18 +229,18 @@ hipError_t launch_tiled(const float* in, const float* P, float* out, int rows, i
 // Returns hipErrorNotSupported when the GEMM is too small for these tiles to fill the chip (the
 // caller then uses the split-contraction kernel of project.hip).
 hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* out,
-                             int rows, int d, int h, int kv, hipStream_t st) {
+                             int rows, int d, int h, int kv, int epilogue, hipStream_t st) {
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
   const long long t128 = (long long)((N + 127) / 128) * ((rows + 127) / 128);
   const long long t64 = (long long)((N + 63) / 64) * ((rows + 63) / 64);
   if (N < 64 || rows < 64) return hipErrorNotSupported;
   if (t128 >= 192)
-    return outp ? launch_tiled<true, 128, 128>(in, P, out, rows, d, h, kv, N, st)
-                : launch_tiled<false, 128, 128>(in, P, out, rows, d, h, kv, N, st);
+    return outp ? launch_tiled<true, 128, 128>(in, P, out, rows, d, h, kv, N, epilogue, st)
+                : launch_tiled<false, 128, 128>(in, P, out, rows, d, h, kv, N, epilogue, st);
   if (t64 >= 256)
-    return outp ? launch_tiled<true, 64, 64>(in, P, out, rows, d, h, kv, N, st)
-                : launch_tiled<false, 64, 64>(in, P, out, rows, d, h, kv, N, st);
+    return outp ? launch_tiled<true, 64, 64>(in, P, out, rows, d, h, kv, N, epilogue, st)
+                : launch_tiled<false, 64, 64>(in, P, out, rows, d, h, kv, N, epilogue, st);
   return hipErrorNotSupported;
 }
 
@@ -252,9 +253,9 @@ hipError_t launch_gemm_tiled_qkv(const float* x, const float* P_q, const float* 
   if (rows < 64) return hipErrorNotSupported;
   const QkvAppend f{P_k, P_v, K, V, lens_in, lens_out, h_kv, cap, v, is_bf16};
   if ((k % 128) == 0 && (v % 128) == 0 && (long long)(ntot / 128) * ((rows + 127) / 128) >= 192)
-    return launch_tiled<false, 128, 128, true>(x, P_q, q, rows, d, h, k, ntot, st, f);
+    return launch_tiled<false, 128, 128, true>(x, P_q, q, rows, d, h, k, ntot, 0, st, f);
   if ((k % 64) == 0 && (v % 64) == 0 && (long long)(ntot / 64) * ((rows + 63) / 64) >= 256)
-    return launch_tiled<false, 64, 64, true>(x, P_q, q, rows, d, h, k, ntot, st, f);
+    return launch_tiled<false, 64, 64, true>(x, P_q, q, rows, d, h, k, ntot, 0, st, f);
   return hipErrorNotSupported;
 }
 

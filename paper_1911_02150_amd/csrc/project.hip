@@ -134,15 +134,18 @@ __device__ __forceinline__ float sum_partials(const float* red0, int e, int stri
 // chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
 template <bool OUT_PROJ, int T>
 __global__ __launch_bounds__(NWAVES * 64)
-void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* __restrict__ out,
-                         int rows, int d, int h, int kv) {
+void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* out,
+                         int rows, int d, int h, int kv, int epilogue) {
   __shared__ float red[NWAVES][T * T];
   const int N = OUT_PROJ ? d : h * kv;
   const int row0 = blockIdx.y * T, n0 = blockIdx.x * T;
   gemm_tile<OUT_PROJ, T>(in, P, rows, d, h, kv, row0, n0, red);
   for (int e = threadIdx.x; e < T * T; e += NWAVES * 64) {
     const int r = e / T, c = e % T;
-    if (row0 + r < rows && n0 + c < N) out[(size_t)(row0 + r) * N + n0 + c] = sum_partials(&red[0][0], e, T * T);
+    if (row0 + r < rows && n0 + c < N) {
+      float* dst = out + (size_t)(row0 + r) * N + n0 + c;
+      *dst = apply_epilogue(sum_partials(&red[0][0], e, T * T), dst, epilogue);
+    }
   }
 }
 
@@ -194,8 +197,8 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
 }  // namespace
 
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
-                          int rows, int d, int h, int kv, hipStream_t st) {
-  const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, st);     // large GEMMs: LDS-tiled kernel
+                          int rows, int d, int h, int kv, int epilogue, hipStream_t st) {
+  const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, epilogue, st);     // large GEMMs: LDS-tiled kernel
   if (big != hipErrorNotSupported) return big;
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
@@ -203,12 +206,12 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
   const dim3 block(NWAVES * 64);
   if (tiles32 >= 512) {          // enough 32x32 tiles for two workgroups per CU
     const dim3 grid((N + 31) / 32, (rows + 31) / 32);
-    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv);
-    else hipLaunchKernelGGL((project_mfma_kernel<false, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
+    else hipLaunchKernelGGL((project_mfma_kernel<false, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
   } else {
     const dim3 grid((N + 15) / 16, (rows + 15) / 16);
-    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
-    else hipLaunchKernelGGL((project_mfma_kernel<false, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv);
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
+    else hipLaunchKernelGGL((project_mfma_kernel<false, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
   }
   return hipGetLastError();
 }

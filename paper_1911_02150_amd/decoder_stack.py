@@ -74,13 +74,17 @@ class DecoderStack:
         hx = B.mqa_stack_layernorm(x)
         return B.mqa_project_qkvo(B.MQA_PROJ_O, hx.view(self.b, 1, self.d), self.E.view(1, -1, self.d))
 
-    # -- one decoding step for the whole stack
+    # -- one decoding step for the whole stack: per layer 8 launches (layernorm, fused q/K/V + append,
+    #    attention (+ merge), output projection added into x, layernorm, W1 with relu, W2 added into x)
     def step(self, tokens: torch.Tensor, t: int) -> torch.Tensor:
         x = self.embed(tokens, t)
-        for l in range(len(self.layers)):
+        dec = B.mha_decode_step if self.multi_head else B.mqa_decode_step
+        for l, w in enumerate(self.layers):
             q = self.attention_append_fused(l, x)
-            B.mqa_stack_add(x, self.attention_attend(l, q))
-            B.mqa_stack_add(x, self.feed_forward(l, x))
+            o = dec(q, self.K[l], self.V[l], self.lens[l])
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_O, o, w["P_o"], out=x, epilogue=B.MQA_EPI_ADD)
+            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
         return self.logits(x)
 
     # -- a whole prompt at once (multi-query only): bulk append + fused causal attention per layer
@@ -98,11 +102,9 @@ class DecoderStack:
             vn = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["P_v"]).view(b, n, self.v)
             B.mqa_append_kv_rows(self.K[l], self.V[l], kn, vn, self.lens[l])
             o = B.mqa_prefill_attention(q, self.K[l], self.V[l], self.lens[l])
-            B.mqa_stack_add(x, B.mqa_project_qkvo(B.MQA_PROJ_O, o.view(b * n, self.h, self.v), w["P_o"]))
-            hx = B.mqa_stack_layernorm(x)
-            u = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["W1"])
-            B.mqa_stack_relu(u)
-            B.mqa_stack_add(x, B.mqa_project_qkvo(B.MQA_PROJ_KV, u, w["W2"]))
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_O, o.view(b * n, self.h, self.v), w["P_o"], out=x, epilogue=B.MQA_EPI_ADD)
+            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
         last = x.view(b, n, self.d)[:, n - 1].contiguous()
         return self.logits(last)
 

@@ -219,6 +219,18 @@ def test_projections(m, rows, d, h, kv):
     assert np.max(np.abs(got.cpu().numpy() - orc.project_kv(x, P_k))) <= 1e-5
     got = m.mqa_project_qkvo(m.MQA_PROJ_O, do, dPo)
     assert np.max(np.abs(got.cpu().numpy() - orc.project_o(o, P_o))) <= 1e-5
+    # epilogues: relu on the way out, and accumulation into what the output holds (a residual stream)
+    got = m.mqa_project_qkvo_ex(m.MQA_PROJ_KV, dx, dPk, epilogue=m.MQA_EPI_RELU)
+    assert np.max(np.abs(got.cpu().numpy() - np.maximum(orc.project_kv(x, P_k), 0))) <= 1e-5
+    assert float(got.min()) >= 0.0
+    res = g.standard_normal((rows, d), dtype=np.float32)
+    acc = torch.from_numpy(res.copy()).to(DEV)
+    m.mqa_project_qkvo_ex(m.MQA_PROJ_O, do, dPo, out=acc, epilogue=m.MQA_EPI_ADD)
+    assert np.max(np.abs(acc.cpu().numpy() - (res + orc.project_o(o, P_o)))) <= 1e-5
+    acc = torch.from_numpy(res[:, :kv].copy()).to(DEV) if kv <= d else None
+    if acc is not None:
+        m.mqa_project_qkvo_ex(m.MQA_PROJ_KV, dx, dPk, out=acc, epilogue=m.MQA_EPI_ADD)
+        assert np.max(np.abs(acc.cpu().numpy() - (res[:, :kv] + orc.project_kv(x, P_k)))) <= 1e-5
 
 
 # ----------------------------------------------------------------- workload 1: one float32 step against a memory
