@@ -204,7 +204,7 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
   const int N = outp ? d : h * kv;
   const long long tiles32 = (long long)((N + 31) / 32) * ((rows + 31) / 32);
   const dim3 block(NWAVES * 64);
-  if (tiles32 >= 512) {          // enough 32x32 tiles for two workgroups per CU
+  if (tiles32 >= 256) {          // enough 32x32 tiles for a workgroup per CU (measured: from 256 tiles on they win)
     const dim3 grid((N + 31) / 32, (rows + 31) / 32);
     if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
     else hipLaunchKernelGGL((project_mfma_kernel<false, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
@@ -225,7 +225,7 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
   if (big != hipErrorNotSupported) return big;
   const int ntot = h * k + h_kv * (k + v);
   const long long tiles32 = (long long)(ntot / 32) * ((rows + 31) / 32);
-  const bool t32 = tiles32 >= 512 && (k % 32) == 0 && (v % 32) == 0;
+  const bool t32 = tiles32 >= 256 && (k % 32) == 0 && (v % 32) == 0;
   const int T = t32 ? 32 : 16;
   const dim3 grid(ntot / T, (rows + T - 1) / T), block(NWAVES * 64);
 #define MQA_QKV(TT, CT) hipLaunchKernelGGL((project_qkv_append_kernel<TT, CT>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
