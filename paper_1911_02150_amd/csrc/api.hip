@@ -59,6 +59,12 @@ int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_b
   chunk = (chunk + 31) & ~31;
   pl->chunk = chunk;
   pl->S = (cap + chunk - 1) / chunk;
+  if (!pl->use_mfma) {
+    // generic kernel, few workgroups: split the heads of a sequence over workgroups as well
+    // (heads are independent, so this needs no merge)
+    const long long blocks = (long long)nseq * pl->S;
+    if (blocks < 128) pl->HG = (int)(G < 256 / blocks ? G : 256 / blocks);
+  }
   return MQA_OK;
 }
 

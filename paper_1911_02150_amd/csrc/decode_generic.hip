@@ -59,9 +59,13 @@ void decode_generic_kernel(DecodeParams p) {
   const int range0 = window_base(L, p.window) + srange * p.chunk;
   const int begin = max(range0, lo);
   const int end = min(range0 + p.chunk, L);
+  // heads of this workgroup: small batches are spread over the chip by giving every workgroup a
+  // few heads only (blockIdx.y), each re-reading the sequence's small K/V
+  const int hpb = (p.G + p.HG - 1) / p.HG;
+  const int hstart = blockIdx.y * hpb, hend = min(p.G, hstart + hpb);
   if (end <= begin) {
     if (p.PS == 0)
-      for (int idx = tid; idx < p.G * v; idx += kThreads) p.o[(size_t)seq * p.G * v + idx] = 0.f;
+      for (int idx = tid; idx < (hend - hstart) * v; idx += kThreads) p.o[((size_t)seq * p.G + hstart) * v + idx] = 0.f;
     return;
   }
   const T* Kseq = reinterpret_cast<const T*>(p.K) + (size_t)seq * p.cap * k;
@@ -75,8 +79,8 @@ void decode_generic_kernel(DecodeParams p) {
   // logits: thread = (position, group of HPT heads): every K row is read kHeads / HPT times
   const int dpos = tid % kTile, dhead0 = (tid / kTile) * HPT;
 
-  for (int h0 = 0; h0 < p.G; h0 += kHeads) {
-    const int nh = min(kHeads, p.G - h0);
+  for (int h0 = hstart; h0 < hend; h0 += kHeads) {
+    const int nh = min(kHeads, hend - h0);
     __syncthreads();
     for (int idx = tid; idx < nh * k4; idx += kThreads) {          // 16-byte loads: one round trip for k <= 128
       float4 x = reinterpret_cast<const float4*>(p.q + ((size_t)seq * p.G + h0) * k)[idx];
@@ -226,7 +230,7 @@ size_t generic_lds_bytes(int k, int v, int tile) {
 hipError_t launch_decode_generic(const DecodeParams& p, int is_bf16, hipStream_t st) {
   const bool wide = generic_lds_bytes(p.k, p.v, 128) <= 144 * 1024;       // k = v = 128: 133 KiB
   const size_t lds = generic_lds_bytes(p.k, p.v, wide ? 128 : 64);
-  const dim3 grid((unsigned)((size_t)p.nseq * p.S)), block(kThreads);
+  const dim3 grid((unsigned)((size_t)p.nseq * p.S), (unsigned)p.HG), block(kThreads);
   void (*kern)(DecodeParams);
   if (wide) kern = is_bf16 ? decode_generic_kernel<uint16_t, 128> : decode_generic_kernel<float, 128>;
   else kern = is_bf16 ? decode_generic_kernel<uint16_t, 64> : decode_generic_kernel<float, 64>;
