@@ -24,7 +24,11 @@ __global__ __launch_bounds__(256)
 void combine_kernel(CombineParams p) {
   const int v4 = p.v >> 2;
   const size_t total = (size_t)p.rows * v4;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  // workgroups are dispatched round-robin over the 8 XCDs; take the rows whose partial states
+  // the same XCD wrote (the decode kernel's workgroup -> sequence mapping), as far as grids agree
+  const unsigned nb = gridDim.x, bid = blockIdx.x;
+  const unsigned wid = ((nb & 7) == 0) ? (bid & 7) * (nb >> 3) + (bid >> 3) : bid;
+  const size_t idx = (size_t)wid * 256 + threadIdx.x;
   if (idx >= total) return;
   const int c4 = (int)(idx % v4);
   const long long row = (long long)(idx / v4);
