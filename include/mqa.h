@@ -26,8 +26,11 @@
  *    growing concat (and its padded fixed-shape variant, Section 4.3 footnote)
  *    is replaced by this capacity + length form.  Values of lens outside
  *    [0,cap] are clamped by the kernels.
- *  - Return value: MQA_OK (0) or a positive MQA_ERR_* code.  On error nothing
- *    has been enqueued.  No call aborts or throws.
+ *  - Return value: MQA_OK (0) or a positive MQA_ERR_* code.  Arguments are
+ *    checked before anything is enqueued, so on MQA_ERR_NULL / _SHAPE / _ALIGN /
+ *    _WORKSPACE / _DTYPE the stream is untouched; MQA_ERR_LAUNCH reports a launch
+ *    the HIP runtime refused (earlier kernels of the same call may already be in
+ *    the stream).  No call aborts or throws.
  *  - Pointers must be 16-byte aligned.
  */
 #ifndef MQA_H
