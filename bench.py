@@ -283,7 +283,21 @@ def cpu_baseline(q, K_bits, V_bits, budget_s=12.0):
         if (el >= budget_s and done >= 8) or done >= 200 * b:
             break
     bytes_done = done * m * 2 * k * 2
+    # the oracle's time for one attention step of the other workloads (float64, same host cores; one run each;
+    # the ragged workload on 64 of its 512 sequences, scaled)
+    others = {}
+    g = np.random.default_rng(0)
+    for name, (bb, hh, mm, scale_up) in {"1_single_step_fp32": (1, 8, 128, 1), "2_incremental_b128": (128, 8, 128, 1),
+                                         "3_decoder_stack_one_layer": (128, 8, 256, 1),
+                                         "5_ragged_large_batch": (64, 64, 4096, 8)}.items():
+        ln = g.integers(1, mm + 1, size=bb) if name.startswith("5") else np.full(bb, mm)
+        qq = g.standard_normal((bb, hh, k), dtype=np.float32)
+        KK, VV = g.standard_normal((bb, mm, k), dtype=np.float32), g.standard_normal((bb, mm, k), dtype=np.float32)
+        t1 = time.perf_counter()
+        orc.mqa_decode(qq, KK, VV, ln)
+        others[name] = {"oracle_attention_ms": (time.perf_counter() - t1) * 1e3 * scale_up}
     return {
+        "other_workloads": others,
         "value": bytes_done / el / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
         "sample": f"{done} of the {b} sequences (m={m}, h={q.shape[1]}) through oracle.mqa_decode in float64, "
                   f"{el:.1f} s; bytes counted as the bf16 K/V bytes of those sequences",
