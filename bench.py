@@ -177,6 +177,21 @@ def other_workloads(m, mi, dev):
         out["2_incremental_b128_" + ("mha" if mh else "mqa")] = {
             "layer_step_us": t, "attention_us": ta, "layer_step_separate_calls_us": graph_time_us(sep),
             "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
+    # the paper's local-attention variants (Section 4.1: current position and the 31 before it), attention only,
+    # at 256 cached positions
+    bq, hq, capq = 128, 8, 256
+    q = torch.randn(bq, hq, 128, device=dev) / 128 ** 0.5
+    o = torch.empty(bq, hq, 128, device=dev)
+    lens = torch.full((bq,), capq, dtype=torch.int32, device=dev)
+    Kq, Vq = (torch.randn(bq, capq, 128, device=dev).to(torch.bfloat16) for _ in range(2))
+    Kh, Vh = (torch.randn(bq, hq, capq, 128, device=dev).to(torch.bfloat16) for _ in range(2))
+    ws = torch.empty(m.mha_decode_workspace_bytes(bq, hq, capq, 128), dtype=torch.uint8, device=dev)
+    out["local_window32_b128_len256"] = {
+        "mqa_attention_us": graph_time_us(lambda st: m.mqa_decode_step_window(q, Kq, Vq, lens, 32, o=o, workspace=ws, stream=st)),
+        "mha_attention_us": graph_time_us(lambda st: m.mha_decode_step_window(q, Kh, Vh, lens, 32, o=o, workspace=ws, stream=st)),
+        "mqa_full_attention_us": graph_time_us(lambda st: m.mqa_decode_step(q, Kq, Vq, lens, o=o, workspace=ws, stream=st)),
+        "mha_full_attention_us": graph_time_us(lambda st: m.mha_decode_step(q, Kh, Vh, lens, o=o, workspace=ws, stream=st))}
+    del Kq, Vq, Kh, Vh
     # workload 3: six such layers at 256 cached positions plus feed-forward, final layernorm, logits, argmax
     # (b = 1024 is the paper's whole batch, which it spread over 8 TPU cores, on the one GPU)
     for mh, bsz in ((False, None), (True, None), (False, 1024), (True, 1024)):
