@@ -49,6 +49,13 @@ def test_long_context_probe_mqa_full_size(m):
     assert bool((o <= Vf.amax(dim=1)[:, None, :] + 1e-4).all()) and bool((o >= Vf.amin(dim=1)[:, None, :] - 1e-4).all())
     assert np.isfinite(got).all()
     print(f"long-context probe MQA: max abs err on {len(sample)} sequences {err:.2e}")
+    # a property that holds at any size (Section 2.1: a weighted sum over the memory positions does not
+    # depend on their order): the same rows of K and V in another order give the same outputs, on all
+    # 64 sequences, although every tile, range and wave then holds different positions
+    perm = torch.from_numpy(mi.rng(4, 997).permutation(cap)).to(DEV)
+    o_perm = m.mqa_decode_step(q, K[:, perm].contiguous(), V[:, perm].contiguous(), lens)
+    torch.cuda.synchronize()
+    assert float((o_perm - o).abs().max()) <= 1e-5
 
 
 def test_long_context_probe_mha_full_size(m):
