@@ -109,6 +109,11 @@ def test_ragged_large_batch_full_size(m):
     ref = orc.mqa_decode(q_np[sample], mi.bf16_bits_to_f64(K_np[sample]), mi.bf16_bits_to_f64(V_np[sample]),
                          lens_np[sample])
     err = _tol_bf16(got[sample], ref, "ragged batch, sampled sequences")
+    # every sequence, not only the sample: the generic kernel (plain float32 FMAs through LDS, no code in common
+    # with the MFMA kernel) must agree on all 512 x 64 output rows
+    o_gen = m.mqa_decode_step(q, K, V, lens, tuning=dict(kernel=1))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(o_gen).all()) and float((o_gen - o).abs().max()) <= 2e-3
     # the forced-large logits are present in the sample: some softmax rows are sharply peaked
     w = orc.mqa_decode_weights(q_np[sample[-1:]], mi.bf16_bits_to_f64(K_np[sample[-1:]]), lens_np[sample[-1:]])[0]
     print(f"ragged batch: lens {lens_np.min()}..{lens_np.max()}, max abs err on {len(sample)} sequences {err:.2e}, "
