@@ -34,10 +34,10 @@ constexpr int GC = 4;        // chunks of contraction indices fetched together
 // them after the barrier this function ends with).  B is addressed inside P [h, C or N, kv]; n0
 // is the tile's first column (OUT_PROJ: of d; else of h*kv), rows / columns past the end are
 // clamped to the last one and must be discarded by the caller.
-template <bool OUT_PROJ, int T>
+template <bool OUT_PROJ, int T, int RB>
 __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const float* __restrict__ P,
                                           int rows, int d, int h, int kv, int row0, int n0,
-                                          float (*red)[T * T]) {
+                                          float (*red)[RB * T * T]) {
   constexpr int TN = T;
   constexpr int CH = 256 / T;                  // contraction indices per chunk (4 per lane group)
   constexpr int NACC = T * T / 64;
@@ -47,30 +47,35 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
   const int N = OUT_PROJ ? d : h * kv;
   const size_t head_stride = (size_t)d * kv;
 
-  // A: this lane's row (clamped; rows past the end are discarded at the store)
-  const float* arow = in + (size_t)min(row0 + i32, rows - 1) * C + 4 * kk;
-  // B: this lane's output column n = n0 + i32 (clamped likewise)
+  // A: this lane's row in each of the RB row blocks (clamped; rows past the end are discarded at the store)
+  const float* arow[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) arow[r] = in + (size_t)min(row0 + r * T + i32, rows - 1) * C + 4 * kk;
+  // B: this lane's output column n = n0 + i32 (clamped likewise); shared by the row blocks
   const int n = min(n0 + i32, N - 1);
   const float* bcol;       // OUT_PROJ: contiguous along c;  else: element (t, n), stride kv along t
   if (OUT_PROJ) bcol = P + (size_t)n * kv + 4 * kk;                      // + (c / kv) * head_stride + c % kv
   else bcol = P + (size_t)(n / kv) * head_stride + (n % kv) + (size_t)(4 * kk) * kv;
 
   typedef __attribute__((ext_vector_type(NACC))) float accv;
-  accv acc;
+  accv acc[RB];
 #pragma unroll
-  for (int r = 0; r < NACC; ++r) acc[r] = 0.f;
+  for (int r = 0; r < RB; ++r)
+#pragma unroll
+    for (int e = 0; e < NACC; ++e) acc[r][e] = 0.f;
 
   const int nchunks = C / CH;                  // C is a multiple of 8; a last half chunk (T = 16) is handled below
   const int tail = C - nchunks * CH;           // 0 or 8 (only when T = 16)
   const int ngroups = (nchunks + (tail ? 1 : 0) + GC - 1) / GC;
-  auto load_group = [&](int grp, float4 (&a)[GC], float4 (&b)[GC]) {
+  auto load_group = [&](int grp, float4 (&a)[RB][GC], float4 (&b)[GC]) {
 #pragma unroll
     for (int e = 0; e < GC; ++e) {
       const int chunk = grp * GC + e;
       // the last, half-filled chunk of a 16-wide contraction: only lane groups kk < 2 hold data
       if (chunk < nchunks || (chunk == nchunks && tail && kk < 2)) {
         const int c0 = chunk * CH;
-        a[e] = *reinterpret_cast<const float4*>(arow + c0);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) a[r][e] = *reinterpret_cast<const float4*>(arow[r] + c0);
         if (OUT_PROJ) {
           const int c = c0 + 4 * kk;                 // 4 consecutive c stay inside one head (kv % 8 == 0)
           b[e] = *reinterpret_cast<const float4*>(P + (size_t)(c / kv) * head_stride + (size_t)n * kv + (c % kv));
@@ -79,29 +84,32 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
           b[e] = make_float4(bp[0], bp[kv], bp[2 * (size_t)kv], bp[3 * (size_t)kv]);
         }
       } else {
-        a[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) a[r][e] = make_float4(0.f, 0.f, 0.f, 0.f);
         b[e] = make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
   };
-  auto multiply = [&](const float4 (&a)[GC], const float4 (&b)[GC]) {
+  auto multiply = [&](const float4 (&a)[RB][GC], const float4 (&b)[GC]) {
 #pragma unroll
-    for (int e = 0; e < GC; ++e) {
-      if constexpr (T == 32) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].x, b[e].x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].y, b[e].y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].z, b[e].z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e].w, b[e].w, acc, 0, 0, 0);
-      } else {
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].x, b[e].x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].y, b[e].y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].z, b[e].z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[e].w, b[e].w, acc, 0, 0, 0);
+    for (int e = 0; e < GC; ++e)
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
+        if constexpr (T == 32) {
+          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].x, b[e].x, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].y, b[e].y, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].z, b[e].z, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].w, b[e].w, acc[r], 0, 0, 0);
+        } else {
+          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].x, b[e].x, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].y, b[e].y, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].z, b[e].z, acc[r], 0, 0, 0);
+          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].w, b[e].w, acc[r], 0, 0, 0);
+        }
       }
-    }
   };
 
-  float4 a0[GC], b0[GC], a1[GC], b1[GC];
+  float4 a0[RB][GC], b0[GC], a1[RB][GC], b1[GC];
   int grp = wave;
   if (grp < ngroups) load_group(grp, a0, b0);
   while (grp < ngroups) {
@@ -114,13 +122,15 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
     grp += NWAVES;
   }
 
-  // D layout: register r of lane (j, g) is tile element (8*(r/4) + 4*g + r%4, j) for the 32x32
-  // tile and (4*g + r, j) for the 16x16 tile
+  // D layout: register e of lane (j, g) is tile element (8*(e/4) + 4*g + e%4, j) for the 32x32
+  // tile and (4*g + e, j) for the 16x16 tile; row block r adds r*T rows
 #pragma unroll
-  for (int r = 0; r < NACC; ++r) {
-    const int trow = (T == 32) ? (8 * (r >> 2) + 4 * kk + (r & 3)) : (4 * kk + r);
-    red[wave][trow * TN + i32] = acc[r];
-  }
+  for (int r = 0; r < RB; ++r)
+#pragma unroll
+    for (int e = 0; e < NACC; ++e) {
+      const int trow = r * T + ((T == 32) ? (8 * (e >> 2) + 4 * kk + (e & 3)) : (4 * kk + e));
+      red[wave][trow * TN + i32] = acc[r][e];
+    }
   __syncthreads();
 }
 
@@ -132,19 +142,20 @@ __device__ __forceinline__ float sum_partials(const float* red0, int e, int stri
 // T = 32: 32x32 tiles (v_mfma_f32_32x32x2_f32, chunks of 8 contraction indices);
 // T = 16: 16x16 tiles (v_mfma_f32_16x16x4_f32, chunks of 16) for GEMMs too small to fill the
 // chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
-template <bool OUT_PROJ, int T>
+template <bool OUT_PROJ, int T, int RB>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* out,
                          int rows, int d, int h, int kv, int epilogue) {
-  __shared__ float red[NWAVES][T * T];
+  constexpr int TM = RB * T;
+  __shared__ float red[NWAVES][TM * T];
   const int N = OUT_PROJ ? d : h * kv;
-  const int row0 = blockIdx.y * T, n0 = blockIdx.x * T;
-  gemm_tile<OUT_PROJ, T>(in, P, rows, d, h, kv, row0, n0, red);
-  for (int e = threadIdx.x; e < T * T; e += NWAVES * 64) {
+  const int row0 = blockIdx.y * TM, n0 = blockIdx.x * T;
+  gemm_tile<OUT_PROJ, T, RB>(in, P, rows, d, h, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < TM * T; e += NWAVES * 64) {
     const int r = e / T, c = e % T;
     if (row0 + r < rows && n0 + c < N) {
       float* dst = out + (size_t)(row0 + r) * N + n0 + c;
-      *dst = apply_epilogue(sum_partials(&red[0][0], e, T * T), dst, epilogue);
+      *dst = apply_epilogue(sum_partials(&red[0][0], e, TM * T), dst, epilogue);
     }
   }
 }
@@ -158,27 +169,28 @@ template <> __device__ __forceinline__ uint16_t cache_value<uint16_t>(float x) {
 // cache type), and lens_out[i] = lens_in[i] + 1.  Column tiles are numbered over q's h*k
 // columns, then K's h_kv*k, then V's h_kv*v (k and v are multiples of T, so a tile belongs to
 // one of them).  A sequence at capacity keeps its cache and its length.
-template <int T, typename CT>
+template <int T, int RB, typename CT>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_qkv_append_kernel(const float* __restrict__ x, const float* __restrict__ P_q,
                                const float* __restrict__ P_k, const float* __restrict__ P_v,
                                float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
                                const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
                                int rows, int d, int h, int h_kv, int cap, int k, int v) {
-  __shared__ float red[NWAVES][T * T];
-  const int row0 = blockIdx.y * T;
+  constexpr int TM = RB * T;
+  __shared__ float red[NWAVES][TM * T];
+  const int row0 = blockIdx.y * TM;
   int n0 = blockIdx.x * T;
   const int nq = h * k, nk = h_kv * k;
   int which = 0;                       // 0: q, 1: K row, 2: V row
   if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; }
   else if (n0 >= nq) { which = 1; n0 -= nq; }
   const int kv = which == 2 ? v : k;
-  gemm_tile<false, T>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
-  for (int e = threadIdx.x; e < T * T; e += NWAVES * 64) {
+  gemm_tile<false, T, RB>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < TM * T; e += NWAVES * 64) {
     const int r = e / T, c = e % T;
     const int row = row0 + r, n = n0 + c;
     if (row >= rows) continue;
-    const float val = sum_partials(&red[0][0], e, T * T);
+    const float val = sum_partials(&red[0][0], e, TM * T);
     if (which == 0) {
       q[(size_t)row * nq + n] = val;
     } else {
@@ -188,7 +200,7 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
       dst[(((size_t)row * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(val);
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x < T && row0 + threadIdx.x < rows) {
+  if (blockIdx.x == 0 && threadIdx.x < TM && row0 + threadIdx.x < rows) {
     const int L = lens_in[row0 + threadIdx.x];
     lens_out[row0 + threadIdx.x] = (L < 0 || L >= cap) ? L : L + 1;
   }
@@ -196,23 +208,37 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
 
 }  // namespace
 
+// Tile choice for the split-contraction kernel: 32x32 tiles when there are at least 256 of them (a
+// workgroup per CU); else, for long contractions, 32x16 tiles (two 16x16 blocks sharing the weight
+// operand: a quarter fewer L1 accesses per MFMA; measured 30 -> 26 us at C = 4096 but 9.4 -> 11.4 us
+// at C = 1024, where the launch is latency-bound and more workgroups help) when there are at least
+// 256 of those; else 16x16 tiles.
+enum TileKind { kTile32, kTile32x16, kTile16 };
+static TileKind pick_tile(long long ncols, int rows, int C) {
+  if (((ncols + 31) / 32) * ((rows + 31) / 32) >= 256) return kTile32;
+  if (C >= 2048 && ((ncols + 15) / 16) * ((rows + 31) / 32) >= 256) return kTile32x16;
+  return kTile16;
+}
+
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, int epilogue, hipStream_t st) {
   const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, epilogue, st);     // large GEMMs: LDS-tiled kernel
   if (big != hipErrorNotSupported) return big;
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
-  const long long tiles32 = (long long)((N + 31) / 32) * ((rows + 31) / 32);
   const dim3 block(NWAVES * 64);
-  if (tiles32 >= 256) {          // enough 32x32 tiles for a workgroup per CU (measured: from 256 tiles on they win)
-    const dim3 grid((N + 31) / 32, (rows + 31) / 32);
-    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
-    else hipLaunchKernelGGL((project_mfma_kernel<false, 32>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
-  } else {
-    const dim3 grid((N + 15) / 16, (rows + 15) / 16);
-    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
-    else hipLaunchKernelGGL((project_mfma_kernel<false, 16>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);
+#define MQA_PROJ(T, RB)                                                                                              \
+  do {                                                                                                               \
+    const dim3 grid((N + T - 1) / T, (rows + RB * T - 1) / (RB * T));                                                \
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, T, RB>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
+    else hipLaunchKernelGGL((project_mfma_kernel<false, T, RB>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);     \
+  } while (0)
+  switch (pick_tile(N, rows, outp ? h * kv : d)) {
+    case kTile32: MQA_PROJ(32, 1); break;
+    case kTile32x16: MQA_PROJ(16, 2); break;
+    default: MQA_PROJ(16, 1); break;
   }
+#undef MQA_PROJ
   return hipGetLastError();
 }
 
@@ -224,14 +250,22 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
                                                is_bf16, st);
   if (big != hipErrorNotSupported) return big;
   const int ntot = h * k + h_kv * (k + v);
-  const long long tiles32 = (long long)(ntot / 32) * ((rows + 31) / 32);
-  const bool t32 = tiles32 >= 256 && (k % 32) == 0 && (v % 32) == 0;
-  const int T = t32 ? 32 : 16;
-  const dim3 grid(ntot / T, (rows + T - 1) / T), block(NWAVES * 64);
-#define MQA_QKV(TT, CT) hipLaunchKernelGGL((project_qkv_append_kernel<TT, CT>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                                           (CT*)K, (CT*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v)
-  if (t32) { if (is_bf16) MQA_QKV(32, uint16_t); else MQA_QKV(32, float); }
-  else     { if (is_bf16) MQA_QKV(16, uint16_t); else MQA_QKV(16, float); }
+  TileKind kind = pick_tile(ntot, rows, d);
+  if (kind == kTile32 && ((k % 32) || (v % 32))) kind = kTile32x16;       // column tiles must not straddle q / K / V
+  const dim3 block(NWAVES * 64);
+#define MQA_QKV(T, RB)                                                                                               \
+  do {                                                                                                               \
+    const dim3 grid(ntot / T, (rows + RB * T - 1) / (RB * T));                                                       \
+    if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<T, RB, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
+                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);     \
+    else hipLaunchKernelGGL((project_qkv_append_kernel<T, RB, float>), grid, block, 0, st, x, P_q, P_k, P_v, q,       \
+                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);                   \
+  } while (0)
+  switch (kind) {
+    case kTile32: MQA_QKV(32, 1); break;
+    case kTile32x16: MQA_QKV(16, 2); break;
+    default: MQA_QKV(16, 1); break;
+  }
 #undef MQA_QKV
   return hipGetLastError();
 }

@@ -202,7 +202,8 @@ def test_append_bit_exact(m, cache, mh):
 @pytest.mark.parametrize("rows,d,h,kv", [(1, 1024, 8, 128), (128, 1024, 8, 128), (37, 72, 3, 40), (5, 8, 1, 8),
                                          (3000, 1032, 8, 136),      # LDS-tiled kernel, 128x128 tiles, ragged edges
                                          (1000, 1032, 8, 136),      # the same with 64x64 tiles
-                                         (130, 264, 64, 128)])      # few rows, very wide output
+                                         (130, 264, 64, 128),       # few rows, very wide output
+                                         (100, 2056, 16, 128)])     # long contraction: 32x16 tiles, ragged rows and tail
 def test_projections(m, rows, d, h, kv):
     g = mi.rng(3000, rows + d)
     x = g.standard_normal((rows, d), dtype=np.float32)
