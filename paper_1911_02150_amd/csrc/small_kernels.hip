@@ -271,19 +271,27 @@ void append_kernel(T* K, T* V, const float* k_new, const float* v_new, int32_t* 
   if (threadIdx.x == 0) lens[i] = L + n;
 }
 
-// Plain streaming read: every 16-byte word is loaded once, folded into a
-// checksum so the loads cannot be dropped.
+// Streaming read: every 16-byte word is loaded once (non-temporal, as the decode kernel reads
+// the cache), folded into a checksum so the loads cannot be dropped.  A wave reads 16 KiB
+// contiguous chunks (16 loads of 1 KiB in flight), the granularity of the decode kernel's tiles.
+typedef __attribute__((ext_vector_type(4))) uint32_t word16;
 __global__ __launch_bounds__(256)
-void stream_read_kernel(const uint4* src, size_t n16, float* sink) {
-  const size_t stride = (size_t)gridDim.x * 256;
+void stream_read_kernel(const word16* src, size_t n16, float* sink) {
+  const size_t nwaves = (size_t)gridDim.x * 4;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   uint32_t acc = 0;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  const size_t nchunks = n16 >> 10;                       // 1024 words = 16 KiB
+  for (size_t c = wave; c < nchunks; c += nwaves) {
+    const word16* base = src + (c << 10) + lane;
+    word16 w[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) w[u] = __builtin_nontemporal_load(base + 64 * u);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc ^= w[u].x ^ w[u].y ^ w[u].z ^ w[u].w;
   }
-  for (; i < n16; i += stride) {
-    const uint4 a = src[i];
+  for (size_t i = (nchunks << 10) + wave * 64 + lane; i < n16; i += nwaves * 64) {      // the last partial chunk
+    const word16 a = __builtin_nontemporal_load(src + i);
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   if (acc == 0x9e3779b9u) sink[blockIdx.x & 4095] = 1.f;   // practically never; keeps the loads live
@@ -334,7 +342,7 @@ hipError_t launch_append(void* K, void* V, const float* k_new, const float* v_ne
 }
 
 hipError_t launch_stream_read(const void* src, size_t bytes, float* sink, hipStream_t st) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3(256 * 16), dim3(256), 0, st, (const uint4*)src, bytes / 16, sink);
+  hipLaunchKernelGGL(stream_read_kernel, dim3(256), dim3(256), 0, st, (const word16*)src, bytes / 16, sink);
   return hipGetLastError();
 }
 
