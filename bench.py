@@ -382,6 +382,10 @@ def main():
     sink = torch.zeros(4096, dtype=torch.float32, device=dev)
     ms_read = time_region(lambda i: m.mqa_stream_read(big, sink), 20, 3)
     stream_read_gbps = big.numel() / (ms_read * 1e-3) / 1e9
+    # the same streaming read over exactly the decode step's K/V bytes: what a kernel that only reads them takes
+    nsame = kv_bytes
+    ms_same = time_region(lambda i: m.mqa_stream_read(big[(i % 3) * nsame:(i % 3 + 1) * nsame], sink), args.steps, args.warmup,
+                          settle_s=0.05)
     big2 = torch.empty_like(big)          # plain copy of known size: the reference for the byte counters
     ms_copy = time_region(lambda i: m.mqa_stream_copy(big, big2), 10, 2)
     stream_copy_gbps = 2 * big.numel() / (ms_copy * 1e-3) / 1e9
@@ -434,6 +438,7 @@ def main():
         "frac_of_peak": value / HBM_PEAK_GBPS, "frac_of_stream_read": value / stream_read_gbps,
         "single_kv_set_step_us_cache_warm": ms_warm * 1e3,
         "stream_read_GBps": stream_read_gbps, "stream_copy_GBps": stream_copy_gbps,
+        "stream_read_of_the_same_kv_bytes_us": ms_same * 1e3,
         "roofline": roofline, "mha": mha, "other_workloads": others, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
