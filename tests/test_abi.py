@@ -123,3 +123,21 @@ def test_beam_entry_points_validate_without_gpu():
     assert re(A, A, A, A, B, B, B, 4, 1, 64, 128, 124, 1, None) == 2
     assert re(A, A, A, U, B, B, B, 4, 1, 64, 128, 128, 1, None) == 3
     assert re(A, A, A, A, B, B, B, 4, 1, 64, 128, 128, 3, None) == 5
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/mqa.h must be usable from C: compile a translation unit that takes the address of
+    every declared function, as C99 with warnings as errors."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    names = declared_functions()
+    src = tmp_path / "use_mqa.c"
+    src.write_text('#include "mqa.h"\n' + "void* table[] = {" + ", ".join(f"(void*){n}" for n in names) + "};\n"
+                   "int main(void) { mqa_tuning t = {0, 0, 0}; return (int)(t.splits + MQA_OK + MQA_PROJ_O - 3 + MQA_EPI_STORE); }\n")
+    inc = os.path.join(ROOT, "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-Wno-pedantic", "-I", inc, "-c", str(src), "-o",
+                        str(tmp_path / "use_mqa.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
