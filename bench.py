@@ -29,6 +29,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# The paper's own decoder timings (Table 2 and the inference-speed paragraph of section 4):
+# another machine, a trained model, an unstated precision and a whole six-layer decoder step.
+# Printed beside this run's numbers as context; never a target and never in vs_baseline.
+PAPER_CONTEXT = {
+    "hardware": "one TPUv2, 8 cores",
+    "workload": "WMT14 EN-DE decoder, 6 layers, d=1024, h=8, k=v=128, batch 1024, source and target length 128",
+    "decoder_us_per_token_greedy": {"multi_head": 46, "multi_query": 3.8,
+                                    "multi_head_local": 23, "multi_query_local": 3.3},
+    "decoder_us_per_token_beam4": {"multi_head": 203, "multi_query": 32,
+                                   "multi_head_local": 47, "multi_query_local": 16},
+    "comparable_here": "other_workloads.3_decoder_stack_*: us_per_token of this build's six-layer self-attention stack",
+    "use": "context only",
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -440,6 +454,7 @@ def main():
         "stream_read_GBps": stream_read_gbps, "stream_copy_GBps": stream_copy_gbps,
         "stream_read_of_the_same_kv_bytes_us": ms_same * 1e3,
         "roofline": roofline, "mha": mha, "other_workloads": others, "cpu_baseline": cpu,
+        "paper_context": PAPER_CONTEXT,
     }
     print(json.dumps(out))
 
