@@ -2,43 +2,61 @@
 // and Section 3): q = einsum('bd,hdk->bhk'), the new K / V rows
 // einsum('bd,dk->bk') (multi-head: 'bd,hdk->bhk') and y = einsum('bhv,hdv->bd').
 // float32 in, float32 products and accumulation on the matrix cores
-// (v_mfma_f32_32x32x2_f32), float32 out.
+// (v_mfma_f32_16x16x4_f32), float32 out.
 //
 // All four are one GEMM out[rows, N] = in[rows, C] . B[C, N] with B addressed
 // inside the projection tensor P [h, d, kv]:
 //   Q / KV / KV_MH : C = d,    N = h*kv, B[t, n]  = P[n/kv][t][n%kv]   (N contiguous)
 //   O              : C = h*kv, N = d,    B[c, t]  = P[c/kv][t][c%kv]   (C contiguous)
 //
-// One workgroup of 8 waves per 32x32 (or, for small GEMMs, 16x16) output tile.  The
-// contraction axis is cut into groups of 4 chunks of 8 (16); wave w takes groups w, w+8, ... (one group in
-// flight while the previous one is multiplied) and the eight partial tiles are
-// summed through LDS.  With at most a few hundred rows these GEMMs are
-// bound by the fp32 matrix rate and by launch latency, not by HBM, so operands
-// are read straight from global memory (L2-resident) in MFMA layout:
+// One workgroup of 8 waves per output tile of RB x CB MFMA blocks of 16x16 (16x16 ... 32x64).
+// The contraction axis is cut into groups of 2 or 4 chunks of 16; wave w takes groups
+// w, w+8, ... (one group in flight while the previous one is multiplied) and the eight partial
+// tiles are summed through LDS.  With at most a few hundred rows these GEMMs are far from
+// HBM-bound (the weights are read once); what limits them is the number of operand loads per
+// MFMA, so operands are read straight from global memory (L2-resident) in MFMA layout and
+// shared between the blocks of a tile:
 //   A operand: lane (i, kk) holds in[row0+i][c0 + 4kk + e], e = 0..3 (one 16-byte load),
-//              and MFMA e of the chunk contracts slots {c0+e, c0+4+e};
-//   B operand: lane (kk, j) holds B[c0 + 4kk + e][n0+j]: four 4-byte loads when N is
-//              contiguous, one 16-byte load when C is.
+//              and MFMA e of the chunk contracts slots {c0+e, c0+4+e, c0+8+e, c0+12+e};
+//   B operand: N contiguous: lane (kk, i) holds B[c0 + 4kk + e][n0 + CB*i + j], j < CB (four
+//              loads of 4*CB bytes; column block j is every CB-th column);
+//              C contiguous: lane (kk, i) holds B[c0 + 4kk + e][n0 + 16 j + i] (CB 16-byte loads).
 #include "common.hpp"
 
 namespace mqa {
 namespace {
 
-typedef __attribute__((ext_vector_type(16))) float floatx16;
-typedef __attribute__((ext_vector_type(4))) float floatx4;
 
 constexpr int NWAVES = 8;
-constexpr int GC = 4;        // chunks of contraction indices fetched together
 
-// One T x T output tile of out = in . B, left as NWAVES partial tiles in `red` (the caller sums
-// them after the barrier this function ends with).  B is addressed inside P [h, C or N, kv]; n0
-// is the tile's first column (OUT_PROJ: of d; else of h*kv), rows / columns past the end are
-// clamped to the last one and must be discarded by the caller.
-template <bool OUT_PROJ, int T, int RB>
+// B operands of one group of GC chunks: w[e][s][j] is the weight of contraction slot 4kk + s of
+// chunk e for column block j (N contiguous: CB adjacent columns per load) or v[e][j] the four
+// slots of column block j (C contiguous: four adjacent contraction indices per load).
+template <bool OUT_PROJ, int GC, int CB> struct BFrag;
+template <int GC, int CB> struct BFrag<false, GC, CB> {
+  typedef float __attribute__((ext_vector_type(CB))) vec;
+  vec w[GC][4];
+};
+template <int GC> struct BFrag<false, GC, 1> {
+  struct vec { float x; __device__ __forceinline__ float operator[](int) const { return x; } };
+  vec w[GC][4];
+};
+template <int GC, int CB> struct BFrag<true, GC, CB> { float4 v[GC][CB]; };
+
+// One (RB*T) x (CB*T) output tile of out = in . B: RB x CB MFMA blocks per wave that share the
+// A operand along a block row and the B operand along a block column (RB + CB operand loads feed
+// RB*CB MFMAs), left as NWAVES partial tiles in `red` (the caller sums them after the barrier
+// this function ends with).  B is addressed inside P [h, C or N, kv]; n0 is the tile's first
+// column (OUT_PROJ: of d; else of h*kv), rows / columns past the end are clamped and must be
+// discarded by the caller.  Column blocks: with C contiguous (OUT_PROJ) block j is columns
+// n0 + j*T + i; with N contiguous block j is columns n0 + CB*i + j, i = 0..T-1, so that a lane's
+// CB weights of one contraction index are adjacent in memory and arrive in one load.
+template <bool OUT_PROJ, int T, int RB, int CB>
 __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const float* __restrict__ P,
                                           int rows, int d, int h, int kv, int row0, int n0,
-                                          float (*red)[RB * T * T]) {
-  constexpr int TN = T;
+                                          float (*red)[RB * T * CB * T]) {
+  constexpr int TN = CB * T;
+  constexpr int GC = (CB == 4) ? 2 : 4;        // chunks of contraction indices fetched together
   constexpr int CH = 256 / T;                  // contraction indices per chunk (4 per lane group)
   constexpr int NACC = T * T / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -51,23 +69,29 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
   const float* arow[RB];
 #pragma unroll
   for (int r = 0; r < RB; ++r) arow[r] = in + (size_t)min(row0 + r * T + i32, rows - 1) * C + 4 * kk;
-  // B: this lane's output column n = n0 + i32 (clamped likewise); shared by the row blocks
-  const int n = min(n0 + i32, N - 1);
-  const float* bcol;       // OUT_PROJ: contiguous along c;  else: element (t, n), stride kv along t
-  if (OUT_PROJ) bcol = P + (size_t)n * kv + 4 * kk;                      // + (c / kv) * head_stride + c % kv
-  else bcol = P + (size_t)(n / kv) * head_stride + (n % kv) + (size_t)(4 * kk) * kv;
+  // B: this lane's output column(s), clamped likewise; shared by the row blocks.
+  // OUT_PROJ: column n[j] of block j, contiguous along c;  else: CB adjacent columns from nb
+  // (inside one head: kv and N are multiples of CB), stride kv along the contraction index
+  int ncol[CB];
+#pragma unroll
+  for (int j = 0; j < CB; ++j) ncol[j] = min(n0 + j * T + i32, N - 1);
+  const int nb = min(n0 + CB * i32, N - CB);
+  const float* bcol = P + (size_t)(nb / kv) * head_stride + (nb % kv) + (size_t)(4 * kk) * kv;
 
   typedef __attribute__((ext_vector_type(NACC))) float accv;
-  accv acc[RB];
+  accv acc[RB][CB];
 #pragma unroll
   for (int r = 0; r < RB; ++r)
 #pragma unroll
-    for (int e = 0; e < NACC; ++e) acc[r][e] = 0.f;
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) acc[r][j][e] = 0.f;
 
   const int nchunks = C / CH;                  // C is a multiple of 8; a last half chunk (T = 16) is handled below
   const int tail = C - nchunks * CH;           // 0 or 8 (only when T = 16)
   const int ngroups = (nchunks + (tail ? 1 : 0) + GC - 1) / GC;
-  auto load_group = [&](int grp, float4 (&a)[RB][GC], float4 (&b)[GC]) {
+  typedef BFrag<OUT_PROJ, GC, CB> bfrag;
+  auto load_group = [&](int grp, float4 (&a)[RB][GC], bfrag& b) {
 #pragma unroll
     for (int e = 0; e < GC; ++e) {
       const int chunk = grp * GC + e;
@@ -76,40 +100,56 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
         const int c0 = chunk * CH;
 #pragma unroll
         for (int r = 0; r < RB; ++r) a[r][e] = *reinterpret_cast<const float4*>(arow[r] + c0);
-        if (OUT_PROJ) {
+        if constexpr (OUT_PROJ) {
           const int c = c0 + 4 * kk;                 // 4 consecutive c stay inside one head (kv % 8 == 0)
-          b[e] = *reinterpret_cast<const float4*>(P + (size_t)(c / kv) * head_stride + (size_t)n * kv + (c % kv));
+          const float* bp = P + (size_t)(c / kv) * head_stride + (c % kv);
+#pragma unroll
+          for (int j = 0; j < CB; ++j) b.v[e][j] = *reinterpret_cast<const float4*>(bp + (size_t)ncol[j] * kv);
         } else {
           const float* bp = bcol + (size_t)c0 * kv;
-          b[e] = make_float4(bp[0], bp[kv], bp[2 * (size_t)kv], bp[3 * (size_t)kv]);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) b.w[e][s] = *reinterpret_cast<const typename bfrag::vec*>(bp + s * (size_t)kv);
         }
       } else {
 #pragma unroll
         for (int r = 0; r < RB; ++r) a[r][e] = make_float4(0.f, 0.f, 0.f, 0.f);
-        b[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if constexpr (OUT_PROJ) {
+#pragma unroll
+          for (int j = 0; j < CB; ++j) b.v[e][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) b.w[e][s] = typename bfrag::vec{};
+        }
       }
     }
   };
-  auto multiply = [&](const float4 (&a)[RB][GC], const float4 (&b)[GC]) {
+  auto mfma = [&](float x, float y, accv c) -> accv {
+    if constexpr (T == 32) return __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, c, 0, 0, 0);
+  };
+  auto multiply = [&](const float4 (&a)[RB][GC], const bfrag& b) {
 #pragma unroll
     for (int e = 0; e < GC; ++e)
 #pragma unroll
-      for (int r = 0; r < RB; ++r) {
-        if constexpr (T == 32) {
-          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].x, b[e].x, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].y, b[e].y, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].z, b[e].z, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[r][e].w, b[e].w, acc[r], 0, 0, 0);
-        } else {
-          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].x, b[e].x, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].y, b[e].y, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].z, b[e].z, acc[r], 0, 0, 0);
-          acc[r] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[r][e].w, b[e].w, acc[r], 0, 0, 0);
+      for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+          if constexpr (OUT_PROJ) {
+            acc[r][j] = mfma(a[r][e].x, b.v[e][j].x, acc[r][j]);
+            acc[r][j] = mfma(a[r][e].y, b.v[e][j].y, acc[r][j]);
+            acc[r][j] = mfma(a[r][e].z, b.v[e][j].z, acc[r][j]);
+            acc[r][j] = mfma(a[r][e].w, b.v[e][j].w, acc[r][j]);
+          } else {
+            acc[r][j] = mfma(a[r][e].x, b.w[e][0][j], acc[r][j]);
+            acc[r][j] = mfma(a[r][e].y, b.w[e][1][j], acc[r][j]);
+            acc[r][j] = mfma(a[r][e].z, b.w[e][2][j], acc[r][j]);
+            acc[r][j] = mfma(a[r][e].w, b.w[e][3][j], acc[r][j]);
+          }
         }
-      }
   };
 
-  float4 a0[RB][GC], b0[GC], a1[RB][GC], b1[GC];
+  float4 a0[RB][GC], a1[RB][GC];
+  bfrag b0, b1;
   int grp = wave;
   if (grp < ngroups) load_group(grp, a0, b0);
   while (grp < ngroups) {
@@ -122,15 +162,19 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
     grp += NWAVES;
   }
 
-  // D layout: register e of lane (j, g) is tile element (8*(e/4) + 4*g + e%4, j) for the 32x32
-  // tile and (4*g + e, j) for the 16x16 tile; row block r adds r*T rows
+  // D layout: register e of lane (i, g) is block element (8*(e/4) + 4*g + e%4, i) for the 32x32
+  // block and (4*g + e, i) for the 16x16 block; row block r adds r*T rows, column block j maps
+  // to tile columns as described above
 #pragma unroll
   for (int r = 0; r < RB; ++r)
 #pragma unroll
-    for (int e = 0; e < NACC; ++e) {
-      const int trow = r * T + ((T == 32) ? (8 * (e >> 2) + 4 * kk + (e & 3)) : (4 * kk + e));
-      red[wave][trow * TN + i32] = acc[r][e];
-    }
+    for (int j = 0; j < CB; ++j)
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) {
+        const int trow = r * T + ((T == 32) ? (8 * (e >> 2) + 4 * kk + (e & 3)) : (4 * kk + e));
+        const int tcol = OUT_PROJ ? j * T + i32 : CB * i32 + j;
+        red[wave][trow * TN + tcol] = acc[r][j][e];
+      }
   __syncthreads();
 }
 
@@ -139,23 +183,23 @@ __device__ __forceinline__ float sum_partials(const float* red0, int e, int stri
          ((red0[4 * stride + e] + red0[5 * stride + e]) + (red0[6 * stride + e] + red0[7 * stride + e]));
 }
 
-// T = 32: 32x32 tiles (v_mfma_f32_32x32x2_f32, chunks of 8 contraction indices);
-// T = 16: 16x16 tiles (v_mfma_f32_16x16x4_f32, chunks of 16) for GEMMs too small to fill the
-// chip with 32x32 tiles.  Lane (i, kk): i = lane % T, kk = lane / T.
-template <bool OUT_PROJ, int T, int RB>
+// T = 16: 16x16 MFMA blocks (v_mfma_f32_16x16x4_f32, chunks of 16 contraction indices), the
+// ones launched; T = 32: 32x32 blocks (v_mfma_f32_32x32x2_f32, chunks of 8).  A workgroup owns
+// an (RB*T) x (CB*T) output tile.  Lane (i, kk): i = lane % T, kk = lane / T.
+template <bool OUT_PROJ, int T, int RB, int CB>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* out,
                          int rows, int d, int h, int kv, int epilogue) {
-  constexpr int TM = RB * T;
-  __shared__ float red[NWAVES][TM * T];
+  constexpr int TM = RB * T, TN = CB * T;
+  __shared__ float red[NWAVES][TM * TN];
   const int N = OUT_PROJ ? d : h * kv;
-  const int row0 = blockIdx.y * TM, n0 = blockIdx.x * T;
-  gemm_tile<OUT_PROJ, T, RB>(in, P, rows, d, h, kv, row0, n0, red);
-  for (int e = threadIdx.x; e < TM * T; e += NWAVES * 64) {
-    const int r = e / T, c = e % T;
+  const int row0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+  gemm_tile<OUT_PROJ, T, RB, CB>(in, P, rows, d, h, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
+    const int r = e / TN, c = e % TN;
     if (row0 + r < rows && n0 + c < N) {
       float* dst = out + (size_t)(row0 + r) * N + n0 + c;
-      *dst = apply_epilogue(sum_partials(&red[0][0], e, TM * T), dst, epilogue);
+      *dst = apply_epilogue(sum_partials(&red[0][0], e, TM * TN), dst, epilogue);
     }
   }
 }
@@ -167,30 +211,30 @@ template <> __device__ __forceinline__ uint16_t cache_value<uint16_t>(float x) {
 // The first three lines of the incremental listings in one launch: q = x . P_q to memory, the
 // new K and V rows x . P_k, x . P_v straight into row lens_in[i] of the caches (rounded to the
 // cache type), and lens_out[i] = lens_in[i] + 1.  Column tiles are numbered over q's h*k
-// columns, then K's h_kv*k, then V's h_kv*v (k and v are multiples of T, so a tile belongs to
-// one of them).  A sequence at capacity keeps its cache and its length.
-template <int T, int RB, typename CT>
+// columns, then K's h_kv*k, then V's h_kv*v (k and v are multiples of the tile width, so a tile
+// belongs to one of them).  A sequence at capacity keeps its cache and its length.
+template <int T, int RB, int CB, typename CT>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_qkv_append_kernel(const float* __restrict__ x, const float* __restrict__ P_q,
                                const float* __restrict__ P_k, const float* __restrict__ P_v,
                                float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
                                const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
                                int rows, int d, int h, int h_kv, int cap, int k, int v) {
-  constexpr int TM = RB * T;
-  __shared__ float red[NWAVES][TM * T];
+  constexpr int TM = RB * T, TN = CB * T;
+  __shared__ float red[NWAVES][TM * TN];
   const int row0 = blockIdx.y * TM;
-  int n0 = blockIdx.x * T;
+  int n0 = blockIdx.x * TN;
   const int nq = h * k, nk = h_kv * k;
   int which = 0;                       // 0: q, 1: K row, 2: V row
   if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; }
   else if (n0 >= nq) { which = 1; n0 -= nq; }
   const int kv = which == 2 ? v : k;
-  gemm_tile<false, T, RB>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
-  for (int e = threadIdx.x; e < TM * T; e += NWAVES * 64) {
-    const int r = e / T, c = e % T;
+  gemm_tile<false, T, RB, CB>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
+  for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
+    const int r = e / TN, c = e % TN;
     const int row = row0 + r, n = n0 + c;
     if (row >= rows) continue;
-    const float val = sum_partials(&red[0][0], e, TM * T);
+    const float val = sum_partials(&red[0][0], e, TM * TN);
     if (which == 0) {
       q[(size_t)row * nq + n] = val;
     } else {
@@ -208,18 +252,33 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
 
 }  // namespace
 
-// Tile choice for the split-contraction kernel: 64x32 tiles (two 32x32 blocks sharing the weight
-// operand) when there are at least 256 of them (a workgroup per CU), else 32x32 tiles likewise; else, for long contractions, 32x16 tiles (two 16x16 blocks sharing the weight
-// operand: a quarter fewer L1 accesses per MFMA; measured 30 -> 26 us at C = 4096 but 9.4 -> 11.4 us
-// at C = 1024, where the launch is latency-bound and more workgroups help) when there are at least
-// 256 of those; else 16x16 tiles.
-enum TileKind { kTile64x32, kTile32, kTile32x16, kTile16 };
-static TileKind pick_tile(long long ncols, int rows, int C) {
-  if (((ncols + 31) / 32) * ((rows + 63) / 64) >= 256) return kTile64x32;
-  if (((ncols + 31) / 32) * ((rows + 31) / 32) >= 256) return kTile32;
-  if (C >= 2048 && ((ncols + 15) / 16) * ((rows + 31) / 32) >= 256) return kTile32x16;
-  return kTile16;
+// Tile shapes of the split-contraction kernel: 16x16 MFMA blocks, RB x CB of them per wave.
+// Larger tiles need fewer operand loads per MFMA (the kernel is bound by the rate of L1 / L2
+// accesses, not by the matrix cores) but give fewer workgroups; the widest tile that still gives
+// about 160 workgroups wins at the decode-sized shapes measured (rows = 128, contraction x
+// columns, microseconds 16x16 -> chosen tile): 1024 x 4096: 33.9 -> 17.3 (32x64); 4096 x 1024:
+// 29.5 -> 22.9 (16x32); 1024 x 1024: 9.5 -> 7.8 (16x32); fused q/K/V 1024 x 1280: 12.2 -> 10.3
+// (16x64), multi-head 1024 x 3072: 21.8 -> 17.6 (32x64).  A second row block only pays when it
+// holds real rows (rows > 16).  32x32 MFMA blocks (T = 32, which gemm_tile also supports) were
+// slower than these at every such shape (1024 x 4096: 21.4) and are not instantiated.
+struct Tile { int RB, CB; };
+static inline long long tiles_of(const Tile& t, long long ncols, int rows) {
+  const long long tm = t.RB * 16, tn = t.CB * 16;
+  return ((ncols + tn - 1) / tn) * ((rows + tm - 1) / tm);
 }
+// colmult: the column width (in floats) that a tile must divide (the fused q/K/V launch: tiles
+// must not straddle q / K / V; else 0)
+static Tile pick_tile(long long ncols, int rows, int colmult) {
+  static const Tile order[] = {{2, 4}, {1, 4}, {2, 2}, {1, 2}, {2, 1}, {1, 1}};
+  for (const Tile& t : order) {
+    if (t.RB == 2 && rows <= 16) continue;
+    if (colmult && (colmult % (t.CB * 16))) continue;
+    if (tiles_of(t, ncols, rows) >= 160) return t;
+  }
+  return (colmult && (colmult % 16)) ? Tile{0, 0} : Tile{1, 1};
+}
+
+#define MQA_TILES(X) X(2, 4) X(1, 4) X(2, 2) X(1, 2) X(2, 1) X(1, 1)
 
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, int epilogue, hipStream_t st) {
@@ -228,19 +287,18 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
   const bool outp = (mode == 3);
   const int N = outp ? d : h * kv;
   const dim3 block(NWAVES * 64);
-#define MQA_PROJ(T, RB)                                                                                              \
-  do {                                                                                                               \
-    const dim3 grid((N + T - 1) / T, (rows + RB * T - 1) / (RB * T));                                                \
-    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, T, RB>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
-    else hipLaunchKernelGGL((project_mfma_kernel<false, T, RB>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);     \
-  } while (0)
-  switch (pick_tile(N, rows, outp ? h * kv : d)) {
-    case kTile64x32: MQA_PROJ(32, 2); break;
-    case kTile32: MQA_PROJ(32, 1); break;
-    case kTile32x16: MQA_PROJ(16, 2); break;
-    default: MQA_PROJ(16, 1); break;
+  const Tile t = pick_tile(N, rows, 0);
+  bool launched = false;
+#define MQA_PROJ(RB_, CB_)                                                                                           \
+  if (!launched && t.RB == RB_ && t.CB == CB_) {                                                                     \
+    const dim3 grid((N + CB_ * 16 - 1) / (CB_ * 16), (rows + RB_ * 16 - 1) / (RB_ * 16));                            \
+    if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16, RB_, CB_>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
+    else hipLaunchKernelGGL((project_mfma_kernel<false, 16, RB_, CB_>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);     \
+    launched = true;                                                                                                 \
   }
+  MQA_TILES(MQA_PROJ)
 #undef MQA_PROJ
+  if (!launched) return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
@@ -252,24 +310,24 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
                                                is_bf16, st);
   if (big != hipErrorNotSupported) return big;
   const int ntot = h * k + h_kv * (k + v);
-  TileKind kind = pick_tile(ntot, rows, d);
-  if ((kind == kTile32 || kind == kTile64x32) && ((k % 32) || (v % 32))) kind = kTile32x16;       // column tiles must not straddle q / K / V
+  // column tiles must not straddle q / K / V: the tile width divides k and v (both multiples of 16)
+  int g = k, r = v;
+  while (r) { const int t2 = g % r; g = r; r = t2; }
+  const Tile t = pick_tile(ntot, rows, g);
   const dim3 block(NWAVES * 64);
-#define MQA_QKV(T, RB)                                                                                               \
-  do {                                                                                                               \
-    const dim3 grid(ntot / T, (rows + RB * T - 1) / (RB * T));                                                       \
-    if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<T, RB, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
+  bool launched = false;
+#define MQA_QKV(RB_, CB_)                                                                                            \
+  if (!launched && t.RB == RB_ && t.CB == CB_) {                                                                     \
+    const dim3 grid(ntot / (CB_ * 16), (rows + RB_ * 16 - 1) / (RB_ * 16));                                          \
+    if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
                                     (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);     \
-    else hipLaunchKernelGGL((project_qkv_append_kernel<T, RB, float>), grid, block, 0, st, x, P_q, P_k, P_v, q,       \
+    else hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, float>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
                             (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);                   \
-  } while (0)
-  switch (kind) {
-    case kTile64x32: MQA_QKV(32, 2); break;
-    case kTile32: MQA_QKV(32, 1); break;
-    case kTile32x16: MQA_QKV(16, 2); break;
-    default: MQA_QKV(16, 1); break;
+    launched = true;                                                                                                 \
   }
+  MQA_TILES(MQA_QKV)
 #undef MQA_QKV
+  if (!launched) return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
