@@ -188,9 +188,14 @@ def other_workloads(m, mi, dev):
     for mh in (False, True):
         fn, attn, sep = layer_step_fn(128, 8, 1024, 128, 128, 128, 128, mh, torch.bfloat16)
         t, ta = graph_time_us(fn), graph_time_us(attn)
+        # the latency curve over the decode loop: attention alone at t cached positions (capacity 128)
+        curve = {}
+        for t_pos in (1, 8, 32, 64, 96):
+            curve[str(t_pos)] = graph_time_us(layer_step_fn(128, 8, 1024, 128, 128, 128, t_pos, mh, torch.bfloat16)[1])
+        curve["128"] = ta
         out["2_incremental_b128_" + ("mha" if mh else "mqa")] = {
             "layer_step_us": t, "attention_us": ta, "layer_step_separate_calls_us": graph_time_us(sep),
-            "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128}
+            "tokens_per_s": 128 / (t * 1e-6), "cached_positions": 128, "attention_us_by_cached_positions": curve}
     # the paper's local-attention variants (Section 4.1: current position and the 31 before it), attention only,
     # at 256 cached positions
     bq, hq, capq = 128, 8, 256
