@@ -203,7 +203,13 @@ def test_append_bit_exact(m, cache, mh):
                                          (3000, 1032, 8, 136),      # LDS-tiled kernel, 128x128 tiles, ragged edges
                                          (1000, 1032, 8, 136),      # the same with 64x64 tiles
                                          (130, 264, 64, 128),       # few rows, very wide output
-                                         (100, 2056, 16, 128)])     # long contraction: 32x16 tiles, ragged rows and tail
+                                         (100, 2056, 16, 128),      # long contraction, ragged rows and tail: 16x64 tiles
+                                         # the other tile shapes of the split-contraction kernel (RB x CB blocks of 16x16):
+                                         (40, 2560, 20, 128),       # 32x32 tiles, both weight layouts
+                                         (40, 264, 1, 1296),        # 32x16 tiles, N contiguous (N = 81 x 16)
+                                         (40, 1296, 2, 64),         # 32x16 tiles, C contiguous
+                                         (100, 2568, 2, 64),        # 32x64 tiles, C contiguous, ragged last column tile
+                                         (128, 1024, 1, 4104)])     # 32x64 tiles, N contiguous, 8 columns in the last tile; contraction tail
 def test_projections(m, rows, d, h, kv):
     g = mi.rng(3000, rows + d)
     x = g.standard_normal((rows, d), dtype=np.float32)
@@ -558,9 +564,11 @@ def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, spli
 
 # ----------------------------------------------------------------- q, K row, V row and the append in one launch
 @pytest.mark.parametrize("b,d,h,k,v,cap,cache,mh", [
-    (128, 1024, 8, 128, 128, 40, "bf16", False),      # workload 2's shape: 16x16 tiles
-    (128, 1024, 8, 128, 128, 40, "bf16", True),
-    (512, 256, 8, 128, 64, 9, "bf16", False),         # enough tiles for the 32x32 variant
+    (128, 1024, 8, 128, 128, 40, "bf16", False),      # workload 2's shape: 16x64 tiles
+    (128, 1024, 8, 128, 128, 40, "bf16", True),       # ... multi-head: 32x64 tiles
+    (40, 136, 26, 48, 16, 5, "f32", False),           # k, v share only a factor 16: 32x16 tiles
+    (40, 136, 78, 32, 32, 5, "bf16", False),          # k = v = 32: 32x32 tiles
+    (512, 256, 8, 128, 64, 9, "bf16", False),
     (5, 72, 3, 48, 16, 7, "f32", False),
     (33, 136, 4, 32, 32, 5, "f32", True),
     (1024, 264, 8, 128, 128, 6, "bf16", False),       # large batch: the LDS-tiled kernel, 64x64 tiles
