@@ -8,8 +8,12 @@ benchmark's CPU-baseline leg call it.
 Everything is numpy float64.  Each function states the passage of the paper
 (arXiv 1911.02150) it writes out.  The paper's method is exact attention with
 the heads dimension removed from K and V, so the oracle is that definition:
-einsum contractions ("broadcast, multiply, sum", Section 2.1) and a softmax
-over the memory positions.  No blocking, fusion or reordering.
+contractions ("broadcast, multiply, sum", Section 2.1) and a softmax over the
+memory positions, with no blocking or fusion of the method's steps.  The
+contractions are numpy matrix products / einsum(optimize=True), which hand the
+sum to the BLAS and so leave the order of a float64 sum to it: results move by
+a few 1e-16 relative between summation orders, and the pins that compare two
+float64 routes allow 1e-15..1e-12 for that reason.
 
 Readings taken where the paper's listings are silent or garbled:
   * Section 2.4 / Section 3 incremental listings project an undefined `M` and
@@ -64,37 +68,57 @@ def dot_product_attention(q, K, V):
 
 
 # --------------------------------------------------------------------------
-# Section 2.2 / Section 3: one query x against a memory M
+# Sections 2.2, 2.3 and 3: whole attention layers, written as loops over the
+# (sequence, head) pairs around the Section 2.1 function.  Every pair is an
+# independent dot-product attention: head j queries with x . P_q[j], reads the
+# memory through (M . P_k[j], M . P_v[j]) -- multi-query: through the one shared
+# (M . P_k, M . P_v), Section 3 -- and adds its output vector times P_o[j]^T
+# (P_o is [h,d,v]: model width before value width) into the layer output.
 # --------------------------------------------------------------------------
+def _masked_attention(Q, K, V, mask=None):
+    """Section 2.1 attention for several queries over one memory: Q [n,k], K [m,k], V [m,v] and an
+    additive mask [n,m] (0 or -inf, Section 2.3) -> [n,v]."""
+    logits = Q @ K.T
+    if mask is not None:
+        logits = logits + mask
+    return softmax64(logits) @ V
+
+
+def _layer(X, M, mask, P_q, P_k, P_v, P_o, shared_kv, kv_round=None):
+    """Y [b,n,d] for X [b,n,d] against M [b,m,d]; mask [b,h,n,m] or None.  shared_kv: P_k [d,k],
+    P_v [d,v] (multi-query); else P_k [h,d,k], P_v [h,d,v] (multi-head)."""
+    X, M, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (X, M, P_q, P_k, P_v, P_o))
+    if mask is not None:
+        mask = np.asarray(mask, dtype=F64)
+    rnd = (lambda a: a) if kv_round is None else kv_round
+    b, n, d = X.shape
+    h = P_q.shape[0]
+    Y = np.zeros((b, n, d), dtype=F64)
+    for i in range(b):
+        if shared_kv:
+            K_i, V_i = rnd(M[i] @ P_k), rnd(M[i] @ P_v)              # one K, V for every head (Section 3)
+        for j in range(h):
+            if not shared_kv:
+                K_i, V_i = rnd(M[i] @ P_k[j]), rnd(M[i] @ P_v[j])    # this head's K, V (Section 2.2)
+            o_ij = _masked_attention(X[i] @ P_q[j], K_i, V_i, None if mask is None else mask[i, j])
+            Y[i] += o_ij @ P_o[j].T
+    return Y
+
+
 def multihead_attention(x, M, P_q, P_k, P_v, P_o):
     """Section 2.2 `MultiheadAttention`: x [d], M [m,d], P_q/P_k [h,d,k],
     P_v/P_o [h,d,v] -> y [d]."""
-    x, M, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (x, M, P_q, P_k, P_v, P_o))
-    q = np.einsum("d,hdk->hk", x, P_q)
-    K = np.einsum("md,hdk->hmk", M, P_k)
-    V = np.einsum("md,hdv->hmv", M, P_v)
-    logits = np.einsum("hk,hmk->hm", q, K)
-    weights = softmax64(logits)
-    o = np.einsum("hm,hmv->hv", weights, V)
-    return np.einsum("hv,hdv->d", o, P_o)
+    x, M = np.asarray(x, dtype=F64), np.asarray(M, dtype=F64)
+    return _layer(x[None, None, :], M[None], None, P_q, P_k, P_v, P_o, shared_kv=False)[0, 0]
 
 
 def multiquery_attention(x, M, P_q, P_k, P_v, P_o):
-    """Section 3 rule applied to the Section 2.2 listing: the letter h is
-    dropped where it indexes K, V, P_k, P_v.  P_k [d,k], P_v [d,v]."""
-    x, M, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (x, M, P_q, P_k, P_v, P_o))
-    q = np.einsum("d,hdk->hk", x, P_q)
-    K = np.einsum("md,dk->mk", M, P_k)
-    V = np.einsum("md,dv->mv", M, P_v)
-    logits = np.einsum("hk,mk->hm", q, K)
-    weights = softmax64(logits)
-    o = np.einsum("hm,mv->hv", weights, V)
-    return np.einsum("hv,hdv->d", o, P_o)
+    """The Section 2.2 layer under the Section 3 rule (K, V, P_k, P_v lose the heads
+    dimension): P_k [d,k], P_v [d,v]."""
+    x, M = np.asarray(x, dtype=F64), np.asarray(M, dtype=F64)
+    return _layer(x[None, None, :], M[None], None, P_q, P_k, P_v, P_o, shared_kv=True)[0, 0]
 
 
-# --------------------------------------------------------------------------
-# Section 2.3 / Section 3: batched (parallel over positions) attention
-# --------------------------------------------------------------------------
 def causal_mask(b, h, n, m=None):
     """Additive mask of Section 2.3: 0 where position j <= i, -inf elsewhere."""
     m = n if m is None else m
@@ -108,31 +132,13 @@ def multihead_attention_batched(X, M, mask, P_q, P_k, P_v, P_o, kv_round=None):
     """Section 2.3 `MultiheadAttentionBatched`: X [b,n,d], M [b,m,d],
     mask [b,h,n,m] -> Y [b,n,d].  `kv_round`, if given, is applied to K and V
     (used to mirror a reduced-precision cache)."""
-    X, M, mask, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (X, M, mask, P_q, P_k, P_v, P_o))
-    Q = np.einsum("bnd,hdk->bhnk", X, P_q)
-    K = np.einsum("bmd,hdk->bhmk", M, P_k)
-    V = np.einsum("bmd,hdv->bhmv", M, P_v)
-    if kv_round is not None:
-        K, V = kv_round(K), kv_round(V)
-    logits = np.einsum("bhnk,bhmk->bhnm", Q, K)
-    weights = softmax64(logits + mask)
-    O = np.einsum("bhnm,bhmv->bhnv", weights, V)
-    return np.einsum("bhnv,hdv->bnd", O, P_o)
+    return _layer(X, M, mask, P_q, P_k, P_v, P_o, shared_kv=False, kv_round=kv_round)
 
 
 def multiquery_attention_batched(X, M, mask, P_q, P_k, P_v, P_o, kv_round=None):
-    """Section 3 `MultiqueryAttentionBatched`: as above with K [b,m,k],
-    V [b,m,v], P_k [d,k], P_v [d,v]."""
-    X, M, mask, P_q, P_k, P_v, P_o = (np.asarray(a, dtype=F64) for a in (X, M, mask, P_q, P_k, P_v, P_o))
-    Q = np.einsum("bnd,hdk->bhnk", X, P_q)
-    K = np.einsum("bmd,dk->bmk", M, P_k)
-    V = np.einsum("bmd,dv->bmv", M, P_v)
-    if kv_round is not None:
-        K, V = kv_round(K), kv_round(V)
-    logits = np.einsum("bhnk,bmk->bhnm", Q, K)
-    weights = softmax64(logits + mask)
-    O = np.einsum("bhnm,bmv->bhnv", weights, V)
-    return np.einsum("bhnv,hdv->bnd", O, P_o)
+    """Section 3 `MultiqueryAttentionBatched`: as above with one K [m,k] and one V [m,v] per
+    sequence, P_k [d,k], P_v [d,v]."""
+    return _layer(X, M, mask, P_q, P_k, P_v, P_o, shared_kv=True, kv_round=kv_round)
 
 
 # --------------------------------------------------------------------------
