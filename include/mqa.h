@@ -59,7 +59,9 @@ typedef enum {
   MQA_PROJ_Q = 0,     /* in [rows,d] . P [h,d,kv] -> out [rows,h,kv]  q = einsum('bd,hdk->bhk')   */
   MQA_PROJ_KV = 1,    /* in [rows,d] . P [d,kv]   -> out [rows,kv]    einsum('bd,dk->bk'); h ignored */
   MQA_PROJ_KV_MH = 2, /* in [rows,d] . P [h,d,kv] -> out [rows,h,kv]  multi-head new rows          */
-  MQA_PROJ_O = 3      /* in [rows,h,kv] . P [h,d,kv] -> out [rows,d]  y = einsum('bhv,hdv->bd')    */
+  MQA_PROJ_O = 3,     /* in [rows,h,kv] . P [h,d,kv] -> out [rows,d]  y = einsum('bhv,hdv->bd')    */
+  MQA_PROJ_LINEAR = 4 /* in [rows,d] . P [d,kv]   -> out [rows,kv]    a plain x.W (the decoder stack's
+                         feed-forward matrices; not part of the attention path); h ignored      */
 } mqa_proj_mode;
 
 /* Optional launch tuning for the decode calls (NULL = library heuristics). */
@@ -70,7 +72,9 @@ typedef struct {
   int32_t flags;    /* MFMA kernel variants, 0 = default.  bit 0: single bf16 term for
                        q; bit 1: single bf16 term for the softmax weights (both
                        faster, less accurate); bit 2: plain instead of
-                       non-temporal cache loads; bit 4: 8 waves per workgroup;
+                       non-temporal cache loads; bit 3: more than 32 heads: 64
+                       heads per workgroup instead of two groups of 32;
+                       bit 4: 8 waves per workgroup;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;
@@ -78,9 +82,13 @@ typedef struct {
 /*
  * The four projections of the incremental listings (Section 2.4 / Section 3):
  * first line (q), the new K and V rows, and the last line (y).  float32 in and
- * out, float32 accumulation.  `rows` is the number of input rows (b for a
- * decode step, b*m when projecting a whole memory M as in the Section 2.2
- * one-query listing).  `kv` is k or v.  `out` is overwritten.
+ * out, float32 accumulation -- except the new K / V rows (MQA_PROJ_KV, _KV_MH
+ * and the K / V part of mqa_project_append_qkv), whose products are summed in
+ * float64 and rounded once to float32: what is then rounded into a bf16 cache
+ * is the correctly rounded projection, whatever the summation order.  `rows`
+ * is the number of input rows (b for a decode step, b*m when projecting a whole
+ * memory M as in the Section 2.2 one-query listing).  `kv` is k or v.  `out` is
+ * overwritten.
  */
 int mqa_project_qkvo(mqa_proj_mode mode, const float* in, const float* P, float* out,
                      int rows, int d, int h, int kv, void* stream);
@@ -99,7 +107,8 @@ int mqa_project_qkvo_ex(mqa_proj_mode mode, const float* in, const float* P, flo
  * The first three lines of the incremental listings plus the concat, in one launch: q = x . P_q
  * is written to q [b,h,k]; the new rows x . P_k, x . P_v go straight into row lens_in[i] of the
  * caches (rounded as in mqa_append_kv) and lens_out[i] = lens_in[i] + 1.  Same results as
- * mqa_project_qkvo (Q, KV or KV_MH) followed by mqa_append_kv up to float32 summation order.
+ * mqa_project_qkvo (Q, KV or KV_MH) followed by mqa_append_kv (q up to float32 summation order;
+ * the cache rows bit for bit).
  *   x [b,d]; P_q [h,d,k]; h_kv = 1 (multi-query): P_k [d,k], P_v [d,v], K [b,cap,k], V [b,cap,v];
  *   h_kv = h (multi-head): P_k [h,d,k], P_v [h,d,v], K [b,h,cap,k], V [b,h,cap,v].
  *   lens_in and lens_out must be different arrays (the workgroups of the launch read lens_in
@@ -244,13 +253,20 @@ int mqa_decode_partials(const float* q, const void* K, const void* V, const int3
 int mqa_decode_combine(const int32_t* lens, float* o, int b, int h, int cap, int k, int v, mqa_dtype dt,
                        void* workspace, size_t workspace_bytes, void* stream, const mqa_tuning* tuning);
 
-/* Workspace sizes in bytes (host-side arithmetic, valid for any tuning). */
+/* Workspace sizes in bytes (host-side arithmetic): an upper bound valid for any tuning ... */
 size_t mqa_decode_workspace_bytes(int b, int h, int cap, int v);
 size_t mha_decode_workspace_bytes(int b, int h, int cap, int v);
+/* ... and exactly what mqa_decode_step / mha_decode_step (library heuristics, no window) use for
+ * this shape: the partial states of the ranges they choose plus the length schedule. */
+size_t mqa_decode_workspace_bytes_default(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head);
 
 /* Number of position ranges the decode calls will use (host-side). multi_head = 0/1. */
 int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head,
                           const mqa_tuning* tuning);
+/* The whole launch plan (host-side): ranges per sequence, positions per range (a multiple of 32)
+ * and head groups, for full (window = 0) or local attention.  Any output pointer may be NULL. */
+int mqa_decode_plan(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head, int window,
+                    const mqa_tuning* tuning, int32_t* splits, int32_t* chunk, int32_t* head_groups);
 
 /*
  * Measurement helpers: a plain streaming read (every 16-byte word of `src` is
@@ -266,15 +282,17 @@ int mqa_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
  * tied token embedding: the model family of Section 4.1), so that a whole decoding loop runs in
  * this library.  Not part of the attention path.  All float32, row-major, device pointers.
  *   layernorm: y[r,:] = (x[r,:] - mean) / sqrt(var + eps), gain 1, bias 0 (biased variance)
- *   embed:     x[r,:] = E[tokens[r],:] + P[positions[r],:]
+ *   embed:     x[r,:] = E[tokens[r],:] + P[positions[r],:], E [vocab,d], P [max_pos,d]; indices outside
+ *              the tables are clamped into them
  *   add:       a[i] += b[i];      relu: a[i] = max(a[i], 0)
- *   argmax:    out[r] = index of the largest x[r,:], the lowest index among equals
- * The feed-forward and the output logits are mqa_project_qkvo calls (KV mode for x.W with
+ *   argmax:    out[r] = index of the largest x[r,:], the lowest index among equals (0 for a row that is
+ *              all NaN or all -inf)
+ * The feed-forward and the output logits are mqa_project_qkvo calls (LINEAR mode for x.W with
  * W [d,n]; O mode with h = 1 for x.E^T with E [vocab,d]).
  */
 int mqa_stack_layernorm(const float* x, float* y, int rows, int d, float eps, void* stream);
 int mqa_stack_embed(const int32_t* tokens, const int32_t* positions, const float* E, const float* P, float* x,
-                    int rows, int d, void* stream);
+                    int rows, int d, int vocab, int max_pos, void* stream);
 int mqa_stack_add(float* a, const float* b, size_t n, void* stream);
 int mqa_stack_relu(float* a, size_t n, void* stream);
 int mqa_stack_argmax(const float* x, int32_t* out, int rows, int n, void* stream);

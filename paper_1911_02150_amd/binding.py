@@ -13,14 +13,15 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libmqa_decode.so")
 
 MQA_F32, MQA_BF16 = 0, 1
-MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O = 0, 1, 2, 3
+MQA_PROJ_Q, MQA_PROJ_KV, MQA_PROJ_KV_MH, MQA_PROJ_O, MQA_PROJ_LINEAR = 0, 1, 2, 3, 4
 MQA_EPI_STORE, MQA_EPI_RELU, MQA_EPI_ADD = 0, 1, 2
 
 EXPORTS = [
     "mqa_project_qkvo", "mqa_project_qkvo_ex", "mqa_project_append_qkv", "mqa_append_kv", "mqa_decode_step", "mha_decode_step",
     "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mha_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
-    "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_num_splits",
+    "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_workspace_bytes_default", "mqa_decode_num_splits",
+    "mqa_decode_plan",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
 ]
@@ -75,11 +76,14 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_decode_workspace_bytes.restype = sz
     lib.mha_decode_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.mha_decode_workspace_bytes.restype = sz
+    lib.mqa_decode_workspace_bytes_default.argtypes = [ci] * 7
+    lib.mqa_decode_workspace_bytes_default.restype = sz
     lib.mqa_decode_num_splits.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp]
+    lib.mqa_decode_plan.argtypes = [ci] * 8 + [tp, vp, vp, vp]
     lib.mqa_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mqa_stream_copy.argtypes = [vp, vp, sz, vp]
     lib.mqa_stack_layernorm.argtypes = [vp, vp, ci, ci, cf, vp]
-    lib.mqa_stack_embed.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp]
+    lib.mqa_stack_embed.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.mqa_stack_add.argtypes = [vp, vp, sz, vp]
     lib.mqa_stack_relu.argtypes = [vp, sz, vp]
     lib.mqa_stack_argmax.argtypes = [vp, vp, ci, ci, vp]
@@ -87,7 +91,7 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
         if name not in ("mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_status_string",
-                        "mqa_decode_beams_workspace_bytes"):
+                        "mqa_decode_beams_workspace_bytes", "mqa_decode_workspace_bytes_default"):
             getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -141,15 +145,36 @@ def mha_decode_workspace_bytes(b, h, cap, v) -> int:
     return int(load_library().mha_decode_workspace_bytes(b, h, cap, v))
 
 
+def mqa_decode_workspace_bytes_default(b, h, cap, k, v, dt, multi_head=False) -> int:
+    """Exactly what the default plan of mqa_decode_step / mha_decode_step uses for this shape."""
+    return int(load_library().mqa_decode_workspace_bytes_default(b, h, cap, k, v, dt, int(multi_head)))
+
+
+def mqa_decode_plan(b, h, cap, k, v, dt, multi_head=False, window=0, tuning=None):
+    """(ranges per sequence, positions per range, head groups) the decode calls will use."""
+    S, chunk, HG = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = load_library().mqa_decode_plan(b, h, cap, k, v, dt, int(multi_head), int(window), _tuning(tuning),
+                                        ctypes.byref(S), ctypes.byref(chunk), ctypes.byref(HG))
+    if rc != 0:
+        raise MqaError("mqa_decode_plan", rc)
+    return S.value, chunk.value, HG.value
+
+
 _ws_cache = {}
 
 
-def _default_workspace(device, nbytes):
-    """Workspace owned by the binding for callers that pass none: one per device, grown on demand."""
-    key = (device.type, device.index)
+def _default_workspace(device, nbytes, stream=None):
+    """Workspace owned by the binding for callers that pass none: one per (device, stream), grown on
+    demand.  A replaced buffer goes back to torch's caching allocator, which keeps it out of other
+    streams' hands until the work queued on the stream it was allocated on has finished -- so
+    allocate it with that stream current."""
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    key = (device.type, device.index, int(stream.cuda_stream))
     ws = _ws_cache.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        with torch.cuda.stream(stream):
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
         _ws_cache[key] = ws
     return ws
 
@@ -174,7 +199,7 @@ def _decode(fn_name, multi_head, q, K, V, lens, o, scale, workspace, stream, tun
         raise ValueError("o must be [b,h,v]")
     if workspace is None:
         nbytes = mha_decode_workspace_bytes(b, h, cap, v) if multi_head else mqa_decode_workspace_bytes(b, h, cap, v)
-        workspace = _default_workspace(q.device, nbytes)
+        workspace = _default_workspace(q.device, nbytes, stream)
     args = [_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K), float(scale)]
     if window is not None:
         args.append(int(window))
@@ -269,7 +294,7 @@ def mqa_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stre
     if o is None:
         o = torch.empty((b, n, h, v), dtype=torch.float32, device=q.device)
     if workspace is None:
-        workspace = _default_workspace(q.device, mqa_decode_workspace_bytes(b, n * h, cap, v))
+        workspace = _default_workspace(q.device, mqa_decode_workspace_bytes(b, n * h, cap, v), stream)
     rc = lib.mqa_prefill_attention(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, n, h, cap, k, v,
                                    _cache_dtype(K), float(scale), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream))
@@ -289,7 +314,7 @@ def mha_prefill_attention(q, K, V, lens, o=None, scale=1.0, workspace=None, stre
     if o is None:
         o = torch.empty((b, h, n, v), dtype=torch.float32, device=q.device)
     if workspace is None:
-        workspace = _default_workspace(q.device, mha_decode_workspace_bytes(b, n * h, cap, v))
+        workspace = _default_workspace(q.device, mha_decode_workspace_bytes(b, n * h, cap, v), stream)
     rc = lib.mha_prefill_attention(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, n, h, cap, k, v,
                                    _cache_dtype(K), float(scale), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream))
@@ -347,7 +372,7 @@ def mqa_decode_step_beams(q, K_src, V_src, lens_src, K_own, V_own, lens_own, o=N
     if o is None:
         o = torch.empty((b, beam, h, v), dtype=torch.float32, device=q.device)
     if workspace is None:
-        workspace = _default_workspace(q.device, mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt))
+        workspace = _default_workspace(q.device, mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt), stream)
     rc = lib.mqa_decode_step_beams(_ptr(q), _ptr(K_src), _ptr(V_src), _ptr(lens_src), _ptr(K_own), _ptr(V_own),
                                    _ptr(lens_own), _ptr(o), b, beam, h, cap_src, cap_own, k, v, dt, float(scale),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
@@ -381,7 +406,7 @@ def _project(fn_name, mode, x, P, out, epilogue, stream):
     lib = load_library()
     _check(x, "in", torch.float32), _check(P, "P", torch.float32)
     rows = x.shape[0]
-    if mode == MQA_PROJ_KV:
+    if mode in (MQA_PROJ_KV, MQA_PROJ_LINEAR):
         d, kv = P.shape
         h, oshape = 1, (rows, kv)
         ok = x.shape == (rows, d)
@@ -414,7 +439,7 @@ def _project(fn_name, mode, x, P, out, epilogue, stream):
 
 
 def mqa_project_qkvo(mode, x, P, out=None, stream=None):
-    """mode Q/KV_MH: x [rows,d], P [h,d,kv] -> [rows,h,kv];  KV: P [d,kv] -> [rows,kv];
+    """mode Q/KV_MH: x [rows,d], P [h,d,kv] -> [rows,h,kv];  KV / LINEAR: P [d,kv] -> [rows,kv];
     O: x [rows,h,kv], P [h,d,kv] -> [rows,d]."""
     return _project("mqa_project_qkvo", mode, x, P, out, None, stream)
 
@@ -458,8 +483,10 @@ def mqa_stack_embed(tokens, positions, E, P, out=None, stream=None):
     rows, d = tokens.numel(), E.shape[1]
     if out is None:
         out = torch.empty((rows, d), dtype=torch.float32, device=E.device)
+    if P.shape[1] != d or positions.numel() != rows:
+        raise ValueError("size mismatch in mqa_stack_embed")
     _rc("mqa_stack_embed", load_library().mqa_stack_embed(_ptr(tokens), _ptr(positions), _ptr(E), _ptr(P), _ptr(out),
-                                                        rows, d, _stream(stream)))
+                                                        rows, d, E.shape[0], P.shape[0], _stream(stream)))
     return out
 
 

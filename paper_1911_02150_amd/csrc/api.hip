@@ -35,11 +35,11 @@ int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_b
     const long long span = (((long long)window + 31) & ~31ll) + 32;
     if (span < cap) cap = (int)span;
   }
-  const bool ok = mfma_shape_ok(G, k, v, is_bf16);
+  const bool ok = mfma_shape_ok(G, k, v, is_bf16, cap_all);
   if (tn.kernel == 2 && !ok) return MQA_ERR_SHAPE;
   pl->use_mfma = ok && tn.kernel != 1;
   pl->HG = 1;
-  if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G) - 1) / mfma_heads_per_block(G);
+  if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G, tn.flags) - 1) / mfma_heads_per_block(G, tn.flags);
   const int min_chunk = pl->use_mfma ? 128 : 256;
   int max_s = (cap + min_chunk - 1) / min_chunk;
   if (max_s > kMaxAutoSplits) max_s = kMaxAutoSplits;
@@ -196,8 +196,8 @@ int plan_beams(int b, int beam, int h, int cap_src, int cap_own, int k, int v, i
 int project_impl(int mode, const float* in, const float* P, float* out, int rows, int d, int h, int kv, int epilogue,
                  void* stream) {
   if (!in || !P || !out) return MQA_ERR_NULL;
-  if (mode < 0 || mode > 3 || epilogue < 0 || epilogue > 2) return MQA_ERR_DTYPE;
-  if (mode == MQA_PROJ_KV) h = 1;
+  if (mode < 0 || mode > 4 || epilogue < 0 || epilogue > 2) return MQA_ERR_DTYPE;
+  if (mode == MQA_PROJ_KV || mode == MQA_PROJ_LINEAR) h = 1;
   if (rows <= 0 || d <= 0 || h <= 0 || kv <= 0) return MQA_ERR_SHAPE;
   if ((d & 7) || (kv & 7)) return MQA_ERR_SHAPE;
   if (misaligned(in) || misaligned(P) || misaligned(out)) return MQA_ERR_ALIGN;
@@ -296,6 +296,34 @@ int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int
   Plan pl;
   const int rc = plan_decode(multi_head ? b * h : b, multi_head ? 1 : h, cap, 0, k, v, dt == MQA_BF16, tn, &pl);
   return rc ? -rc : pl.S;
+}
+
+int mqa_decode_plan(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head, int window,
+                    const mqa_tuning* tuning, int32_t* splits, int32_t* chunk, int32_t* head_groups) {
+  if (b <= 0 || h <= 0 || cap <= 0 || k <= 0 || v <= 0 || window < 0) return MQA_ERR_SHAPE;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  Tuning tn;
+  if (tuning) {
+    tn.splits = tuning->splits;
+    tn.kernel = tuning->kernel;
+    tn.flags = tuning->flags;
+  }
+  Plan pl;
+  const int rc = plan_decode(multi_head ? b * h : b, multi_head ? 1 : h, cap, window, k, v, dt == MQA_BF16, tn, &pl);
+  if (rc) return rc;
+  if (splits) *splits = pl.S;
+  if (chunk) *chunk = pl.chunk;
+  if (head_groups) *head_groups = pl.HG;
+  return MQA_OK;
+}
+
+size_t mqa_decode_workspace_bytes_default(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head) {
+  if (b <= 0 || h <= 0 || cap <= 0 || k <= 0 || v <= 0) return 0;
+  Plan pl;
+  const long long nseq = multi_head ? (long long)b * h : b;
+  if (plan_decode((int)nseq, multi_head ? 1 : h, cap, 0, k, v, dt == MQA_BF16, Tuning{}, &pl)) return 0;
+  const size_t part = pl.S > 1 ? partial_bytes((long long)b * h, pl.S, v) : 0;
+  return ((part + 15) & ~(size_t)15) + (size_t)nseq * sizeof(int32_t);      // + the schedule of the groups
 }
 
 int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
@@ -471,32 +499,37 @@ void mqa_debug_timeline(long long* p) { g_timeline = p; }
 int mqa_stack_layernorm(const float* x, float* y, int rows, int d, float eps, void* stream) {
   if (!x || !y) return MQA_ERR_NULL;
   if (rows <= 0 || d <= 0) return MQA_ERR_SHAPE;
+  if (misaligned(x) || misaligned(y)) return MQA_ERR_ALIGN;
   return launch_layernorm(x, y, rows, d, eps, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
 }
 
 int mqa_stack_embed(const int32_t* tokens, const int32_t* positions, const float* E, const float* P, float* x,
-                    int rows, int d, void* stream) {
+                    int rows, int d, int vocab, int max_pos, void* stream) {
   if (!tokens || !positions || !E || !P || !x) return MQA_ERR_NULL;
-  if (rows <= 0 || d <= 0) return MQA_ERR_SHAPE;
-  return launch_embed(tokens, positions, E, P, x, rows, d, static_cast<hipStream_t>(stream)) == hipSuccess
+  if (rows <= 0 || d <= 0 || vocab <= 0 || max_pos <= 0) return MQA_ERR_SHAPE;
+  if (misaligned(tokens) || misaligned(positions) || misaligned(E) || misaligned(P) || misaligned(x)) return MQA_ERR_ALIGN;
+  return launch_embed(tokens, positions, E, P, x, rows, d, vocab, max_pos, static_cast<hipStream_t>(stream)) == hipSuccess
              ? MQA_OK : MQA_ERR_LAUNCH;
 }
 
 int mqa_stack_add(float* a, const float* b, size_t n, void* stream) {
   if (!a || !b) return MQA_ERR_NULL;
   if (n == 0) return MQA_ERR_SHAPE;
+  if (misaligned(a) || misaligned(b)) return MQA_ERR_ALIGN;
   return launch_add(a, b, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
 }
 
 int mqa_stack_relu(float* a, size_t n, void* stream) {
   if (!a) return MQA_ERR_NULL;
   if (n == 0) return MQA_ERR_SHAPE;
+  if (misaligned(a)) return MQA_ERR_ALIGN;
   return launch_relu(a, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
 }
 
 int mqa_stack_argmax(const float* x, int32_t* out, int rows, int n, void* stream) {
   if (!x || !out) return MQA_ERR_NULL;
   if (rows <= 0 || n <= 0) return MQA_ERR_SHAPE;
+  if (misaligned(x)) return MQA_ERR_ALIGN;          // rows of n % 4 == 0 floats are read with 16-byte loads
   return launch_argmax(x, out, rows, n, static_cast<hipStream_t>(stream)) == hipSuccess ? MQA_OK : MQA_ERR_LAUNCH;
 }
 

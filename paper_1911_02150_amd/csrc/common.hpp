@@ -80,8 +80,8 @@ struct Tuning {
 };
 
 // decode_mfma.hip: bf16 cache, k = v = 128; 16 or 32 heads per workgroup.
-bool mfma_shape_ok(int G, int k, int v, int is_bf16);
-int mfma_heads_per_block(int G);
+bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap);
+int mfma_heads_per_block(int G, int flags);
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
 // both segments in one launch (p.seg1 filled in, 32 heads per workgroup in both); p.order must be null
 hipError_t launch_decode_mfma_two(const DecodeParams& p, long long nblocks0, long long nblocks1, hipStream_t st);
@@ -109,10 +109,6 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
 // gemm.hip: the same GEMM for large row counts / wide outputs (hipErrorNotSupported: too small, use launch_project's own kernel)
 hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* out,
                              int rows, int d, int h, int kv, int epilogue, hipStream_t st);
-hipError_t launch_gemm_tiled_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
-                                 float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
-                                 int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
-                                 hipStream_t st);
 hipError_t launch_project_qkv_append(const float* x, const float* P_q, const float* P_k, const float* P_v,
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
@@ -121,7 +117,7 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
 // stack_kernels.hip
 hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps, hipStream_t st);
 hipError_t launch_embed(const int32_t* tokens, const int32_t* pos, const float* E, const float* P, float* x,
-                        int rows, int d, hipStream_t st);
+                        int rows, int d, int vocab, int max_pos, hipStream_t st);
 hipError_t launch_add(float* a, const float* b, size_t n, hipStream_t st);
 hipError_t launch_relu(float* a, size_t n, hipStream_t st);
 hipError_t launch_argmax(const float* x, int32_t* out, int rows, int n, hipStream_t st);

@@ -17,7 +17,6 @@ constexpr int kHeads = 8;     // heads per pass
 // positions per tile: TILE = 64, or 128 when k and v are small enough for the LDS (fewer
 // dependent round trips per position: these launches are latency-bound)
 constexpr int kThreads = 256;
-constexpr int kMaxDim = 256;
 
 // four consecutive cache elements as floats (row offsets are multiples of 4 elements)
 __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }

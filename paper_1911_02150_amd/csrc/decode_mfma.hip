@@ -9,9 +9,8 @@
 //   grid  = nseq * S * HG workgroups (sequence, position range, group of 16*HB heads; HB = 1 or 2).
 //           More than 32 heads are split into head groups: the groups of one (sequence, range)
 //           are neighbouring work items on one XCD and read the same tiles at about the same
-//           time, so with cacheable loads the second read is served by L2.  (One wave holding
-//           64 heads needs 128 accumulator registers and a workgroup per CU and measured no
-//           faster; two teams of waves in one workgroup measured slower.)
+//           time, so with cacheable loads the second read is served by L2.  (Two teams of waves
+//           in one workgroup measured slower.)
 //           With an order array (ragged batches) the sequences are taken longest first.
 //   block = NW independent wavefronts; wave w takes the 32-position tiles
 //           w, w+NW, ... of the range, so the block streams its range front to back.
@@ -42,9 +41,16 @@
 //
 // Rows at and beyond the sequence length are never used: their logits are set
 // to -inf and their V registers to zero before the second MFMA, so the cache
-// may hold anything (NaN included) there.  Loads are clamped to the capacity,
-// not to the length, which lets the first tile be requested before the length
-// has arrived from memory.
+// may hold anything (NaN included) there.  K and V are read through buffer
+// descriptors that span the sequence's capacity (the hardware returns zeros
+// beyond it), not its length, which lets the first tile be requested before the
+// length has arrived from memory.
+//
+// 64 heads in one wave (HB = 4, a tuning flag): the accumulators alone are 128
+// registers, so the kernel then runs one wave per SIMD with the q operands read
+// from LDS per tile.  Measured no faster than two head groups of 32 whose second
+// read of a tile is an L2 hit, unless the weights are also kept as single bf16
+// terms; not the default.
 #include "common.hpp"
 
 namespace mqa {
@@ -60,6 +66,11 @@ namespace {
 constexpr int kD = 128;              // k = v = 128
 constexpr int kRowU4 = kD * 2 / 16;  // 16-byte words per cache row (16)
 constexpr int kOPitch = kD + 4;      // LDS row pitch (floats) of the merge buffers
+// Buffer descriptors (CDNA3/4 ISA guide, buffer resource word 3): raw 32-bit-element buffer,
+// no swizzle; kNoTile is an offset no cache reaches (capacities are below 2^23 rows of 256 B).
+constexpr int kBufferWord3 = 0x00020000;
+constexpr uint32_t kNoTile = 0x80000000u;
+constexpr float kSlack = 8.f;        // log2 of the largest softmax weight kept before the running state is rescaled
 
 __device__ __forceinline__ floatx4 mfma16(const u32x4& a, const u32x4& b, const floatx4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
@@ -102,7 +113,7 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
 // shared by the hypotheses of a source, then each hypothesis' own rows); workgroups from
 // p.nblocks0 on take the second segment's cache, grouping and slots.
 template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false>
-__global__ __launch_bounds__(NW * 64, 2)
+__global__ __launch_bounds__(NW * 64, HB == 4 ? 1 : 2)
 void decode_mfma_kernel(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -145,31 +156,40 @@ void decode_mfma_kernel(DecodeParams p) {
   const u32x4* Kbase = reinterpret_cast<const u32x4*>(sg.K) + (size_t)seq * sg.cap * kRowU4;
   const u32x4* Vbase = reinterpret_cast<const u32x4*>(sg.V) + (size_t)seq * sg.cap * kRowU4;
   const int krow_in_tile = 4 * (i16 & 3) + (i16 >> 2);
-  const int rmax = sg.cap - 1;
 
-  // A tile past the end of the range is "fetched" from one fixed in-bounds address by all
-  // lanes (a single cached line), so the prefetch needs no branch and costs no bandwidth.
-  // (Keeping a second tile per wave in flight was measured slower: the memory pipeline
-  // accepts the extra requests no sooner.)
+  // Tile loads go through buffer descriptors of the sequence's K and V (base, cap rows of 256 B):
+  // a lane's address is a per-lane constant plus the tile's byte offset, both in the 32-bit VGPR
+  // offset that the hardware checks against the buffer size, so rows at and beyond the capacity
+  // read as zeros without touching memory.  That makes the tile that straddles the capacity, the
+  // speculative first tile and the "tile" a wave requests after its last one (offset kNoTile:
+  // nothing is fetched) all the same branch-free code, and leaves four integer additions per tile
+  // as the whole address arithmetic.  (Keeping a second tile per wave in flight was measured
+  // slower: the memory pipeline accepts the extra requests no sooner.)
   struct Tile { u32x4 kr[2][4]; u32x4 vr[8]; };
   Tile tb;
-  auto load_k = [&](Tile& tl, int t, bool real) {
-    const int p0 = begin + 32 * t;
+  const __amdgpu_buffer_rsrc_t Kbuf = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u32x4*>(Kbase), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
+  const __amdgpu_buffer_rsrc_t Vbuf = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u32x4*>(Vbase), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
+  const uint32_t klane = (uint32_t)(krow_in_tile * kRowU4 + g) * 16u;      // row krow_in_tile, 16-byte chunk g
+  const uint32_t vlane = (uint32_t)(g * kRowU4 + i16) * 16u;               // row g, 16-byte chunk i16
+  constexpr int kAuxK = NTL ? 2 : 0, kAuxV = NTL ? 2 : 0;                   // non-temporal hint
+  auto tile_offset = [&](int t, bool wanted) -> uint32_t {                  // wave-uniform
+    return wanted ? (uint32_t)(begin + 32 * t) * (uint32_t)(kRowU4 * 16) : kNoTile;
+  };
+  auto load_k = [&](Tile& tl, uint32_t toff) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const int row = real ? min(p0 + 16 * u + krow_in_tile, rmax) : begin;
-      const u32x4* src = Kbase + (size_t)row * kRowU4 + (real ? g : 0);
+      const uint32_t off = klane + toff + (uint32_t)u * (16u * kRowU4 * 16u);        // rows 16u.. of the tile
 #pragma unroll
-      for (int s4 = 0; s4 < 4; ++s4) tl.kr[u][s4] = ld16<NTL>(src + (real ? 4 * s4 : 0));
+      for (int s4 = 0; s4 < 4; ++s4)
+        tl.kr[u][s4] = __builtin_amdgcn_raw_buffer_load_b128(Kbuf, off + 64u * s4, 0, kAuxK);
     }
   };
-  auto load_v = [&](Tile& tl, int t, bool real) {
-    const int p0 = begin + 32 * t;
+  auto load_v = [&](Tile& tl, uint32_t toff) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int row = real ? min(p0 + 4 * e + g, rmax) : begin;
-      tl.vr[e] = ld16<NTL>(Vbase + (size_t)row * kRowU4 + (real ? i16 : 0));
-    }
+    for (int e = 0; e < 8; ++e)
+      tl.vr[e] = __builtin_amdgcn_raw_buffer_load_b128(Vbuf, vlane + toff + (uint32_t)e * (4u * kRowU4 * 16u), 0, kAuxV);
   };
 
   MQA_STAMP(0);
@@ -196,9 +216,8 @@ void decode_mfma_kernel(DecodeParams p) {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   if (p.window == 0) {
-    const bool real = begin + 32 * wave <= rmax;
-    load_k(tb, wave, real);
-    load_v(tb, wave, real);
+    load_k(tb, tile_offset(wave, true));
+    load_v(tb, tile_offset(wave, true));
   }
   MQA_STAMP(1);
   int L = sg.lens[seq / sg.lens_div];
@@ -208,9 +227,8 @@ void decode_mfma_kernel(DecodeParams p) {
   const int lo = window_lo(L, p.window);
   if (p.window > 0) {
     begin += window_base(L, p.window);
-    const bool real = begin + 32 * wave <= rmax;
-    load_k(tb, wave, real);
-    load_v(tb, wave, real);
+    load_k(tb, tile_offset(wave, true));
+    load_v(tb, tile_offset(wave, true));
   }
   // Causal rows (prefill of n queries per sequence): row r = query r / h, at position L - n + r / h,
   // attends to positions <= its own.  `end` is the largest such limit in this workgroup.
@@ -280,6 +298,11 @@ void decode_mfma_kernel(DecodeParams p) {
     const bool more = tn < ntiles;
 
     // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
+    // (up to 32 heads the q operands stay in registers for the whole range; with 64 heads they
+    // would take 128 registers, so they are read from LDS tile by tile: the opaque copy of the
+    // pointer keeps the compiler from hoisting the reads out of the loop)
+    const u32x4* qs_t = qs;
+    if constexpr (HB == 4) asm volatile("" : "+v"(qs_t));
     floatx4 sc[2][HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
@@ -287,20 +310,20 @@ void decode_mfma_kernel(DecodeParams p) {
       sc[1][hb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s4 = 0; s4 < 4; ++s4) {
-        const u32x4 qh = qs[(hb * 4 + s4) * 64 + lane];
+        const u32x4 qh = qs_t[(hb * 4 + s4) * 64 + lane];
         sc[0][hb] = mfma16(tl.kr[0][s4], qh, sc[0][hb]);
         sc[1][hb] = mfma16(tl.kr[1][s4], qh, sc[1][hb]);
         if (QSPLIT) {
-          const u32x4 ql = qs[QOPS + (hb * 4 + s4) * 64 + lane];
+          const u32x4 ql = qs_t[QOPS + (hb * 4 + s4) * 64 + lane];
           sc[0][hb] = mfma16(tl.kr[0][s4], ql, sc[0][hb]);
           sc[1][hb] = mfma16(tl.kr[1][s4], ql, sc[1][hb]);
         }
       }
     }
-    load_k(tl, tn, more);       // K registers are free: fetch the tile that will use them next
+    load_k(tl, tile_offset(tn, more));       // K registers are free: fetch the tile that will use them next
     if (t == wave) MQA_STAMP(3);
 
-    if (tail) {                 // ragged end of the range / start of a window: drop positions outside [lo, end)
+    if (__builtin_expect(tail, 0)) {   // ragged end of the range / start of a window: drop positions outside [lo, end)
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -325,17 +348,22 @@ void decode_mfma_kernel(DecodeParams p) {
                        fmaxf(fmaxf(sc[1][hb][0], sc[1][hb][1]), fmaxf(sc[1][hb][2], sc[1][hb][3])));
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      // The reference value the exponentials are taken against is only moved up when some row's
+      // maximum has grown by more than 2^kSlack (lazy rescaling): weights then reach at most
+      // 2^kSlack instead of 1, which float32 sums and the bf16 hi/lo split carry without loss,
+      // and the 32 accumulator registers are rescaled on a few tiles only, not on most of them.
+      // Any reference is a valid softmax state: the merges below only need (reference, sum, acc).
       const float mnew = fmaxf(m_run[hb], mx);
-      // a causal row may have seen nothing yet (maximum still -inf): subtract 0 instead, so that
-      // its weights come out as 2^(-inf) = 0 rather than 2^(-inf + inf)
-      const float mref = mnew == -INFINITY ? 0.f : mnew;
-      if (__any(mnew > m_run[hb])) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - mref);
+      if (__any(mnew > m_run[hb] + kSlack)) {
+        // a causal row may have seen nothing yet (maximum still -inf): subtract 0 instead, so that
+        // its weights come out as 2^(-inf) = 0 rather than 2^(-inf + inf)
+        const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - (mnew == -INFINITY ? 0.f : mnew));
         l_run[hb] *= alpha;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[hb][j] *= alpha;
         m_run[hb] = mnew;
       }
+      const float mref = m_run[hb] == -INFINITY ? 0.f : m_run[hb];
       float pe[8];
       float sum = 0.f;
 #pragma unroll
@@ -376,7 +404,7 @@ void decode_mfma_kernel(DecodeParams p) {
         }
       }
     }
-    load_v(tl, tn, more);
+    load_v(tl, tile_offset(tn, more));
     if (t == wave) MQA_STAMP(4);
   };
   for (int t = wave; t < ntiles; t += NW) process(tb, t, t + NW);
@@ -458,7 +486,7 @@ template <int HB, int NW>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
   const size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
-  p.merge_alias = nblocks > 256 ? 1 : 0;      // more workgroups than CUs: keep LDS small
+  p.merge_alias = (nblocks > 256 || HB == 4) ? 1 : 0;      // more workgroups than CUs (or 64 heads): keep LDS small
   const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 5 * NW * 16 * HB) * sizeof(float);
   const size_t lds = p.merge_alias ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
@@ -479,9 +507,10 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
     const int slot = (flags & 3) | (ntl ? 4 : 0);
+    const size_t most = HB == 4 ? merge_bytes : q_bytes + merge_bytes;     // 64 heads: always the aliased layout
     if (!done[dev][slot]) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)(q_bytes + merge_bytes));
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
       if (e != hipSuccess) return e;
       done[dev][slot] = true;
     }
@@ -492,12 +521,12 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
 
 }  // namespace
 
-bool mfma_shape_ok(int G, int k, int v, int is_bf16) {
+bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap) {
   (void)G;
-  return is_bf16 && k == kD && v == kD;
+  return is_bf16 && k == kD && v == kD && cap < (1 << 23);      // a sequence's cache is addressed with 31-bit byte offsets
 }
 
-int mfma_heads_per_block(int G) { return G <= 16 ? 16 : 32; }
+int mfma_heads_per_block(int G, int flags) { return G <= 16 ? 16 : (G > 32 && (flags & 8)) ? 64 : 32; }
 
 hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, long long nblocks1, hipStream_t st) {
   constexpr int HB = 2, NW = 4;
@@ -529,7 +558,9 @@ hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, 
 
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
   const bool wide = (flags & 16) != 0;       // 8 waves per workgroup instead of 4
-  if (mfma_heads_per_block(p.G) == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
+  const int hpb = mfma_heads_per_block(p.G, flags);
+  if (hpb == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
+  if (hpb == 64) return launch_hb<4, 4>(p, flags, st);
   return wide ? launch_hb<2, 8>(p, flags, st) : launch_hb<2, 4>(p, flags, st);
 }
 

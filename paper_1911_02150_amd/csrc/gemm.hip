@@ -30,25 +30,12 @@ constexpr int kAPitch = BK + 4;          // As[row][c], Bs[n][c]
 
 template <int BN> constexpr int b_tile_floats(bool kcontig) { return kcontig ? BN * kAPitch : BK * (BN + 4); }
 
-// Optional epilogue of the fused q / K row / V row projection (QKV = true, B_KCONTIG = false): the
-// column tiles are numbered over q's h*kv columns, then K's h_kv*kv, then V's h_kv*v (all
-// multiples of BN); K and V tiles are rounded and stored into row lens_in[row] of the caches.
-struct QkvAppend {
-  const float* P_k;
-  const float* P_v;
-  void* K;
-  void* V;
-  const int32_t* lens_in;
-  int32_t* lens_out;
-  int h_kv, cap, v, is_bf16;
-};
-
 // B_KCONTIG = false: B[c][n] = P[(n / kv) * d * kv + c * kv + n % kv]   (C = d, N = h * kv)
 // B_KCONTIG = true : B[c][n] = P[(c / kv) * d * kv + n * kv + c % kv]   (C = h * kv, N = d)
-template <bool B_KCONTIG, int BM, int BN, bool QKV = false>
+template <bool B_KCONTIG, int BM, int BN>
 __global__ __launch_bounds__(256)
-void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P_in, float* out,
-                       int rows, int d, int h_in, int kv_in, int epilogue, QkvAppend f) {
+void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P, float* out,
+                       int rows, int d, int h, int kv, int epilogue) {
   constexpr int RB = BM / 64, CB = BN / 64;            // 32x32 blocks per wave in each direction
   constexpr int A_F4 = BM * BK / 4 / 256;              // float4 loads per thread per K-step
   constexpr int B_F4 = BN * BK / 4 / 256;
@@ -60,16 +47,8 @@ void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i32 = lane & 31, kk = lane >> 5;
-  const float* P = P_in;
-  int h = h_in, kv = kv_in;
   const int row0 = blockIdx.y * BM;
-  int n0 = blockIdx.x * BN;
-  int which = 0;                               // QKV: 0 = q, 1 = K row, 2 = V row
-  if constexpr (QKV) {
-    const int nq = h_in * kv_in, nk = f.h_kv * kv_in;
-    if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; P = f.P_v; h = f.h_kv; kv = f.v; }
-    else if (n0 >= nq) { which = 1; n0 -= nq; P = f.P_k; h = f.h_kv; }
-  }
+  const int n0 = blockIdx.x * BN;
   const int C = B_KCONTIG ? h * kv : d;
   const int N = B_KCONTIG ? d : h * kv;
   const int wrow = (wave >> 1) * (BM / 2), wcol = (wave & 1) * (BN / 2);
@@ -182,32 +161,17 @@ void gemm_tiled_kernel(const float* __restrict__ in, const float* __restrict__ P
       for (int e = 0; e < 16; ++e) {
         const int row = row0 + wrow + 32 * r + 8 * (e >> 2) + 4 * kk + (e & 3);
         if (row >= rows || n >= N) continue;
-        if (!QKV || which == 0) {
-          float* dst = out + (size_t)row * N + n;
-          *dst = apply_epilogue(acc[r][c][e], dst, epilogue);
-        } else {
-          const int L = f.lens_in[row];
-          if (L < 0 || L >= f.cap) continue;                       // at capacity: the cache is left as it is
-          const size_t at = (((size_t)row * f.h_kv + n / kv) * f.cap + L) * kv + (n % kv);
-          void* dst = which == 1 ? f.K : f.V;
-          if (f.is_bf16) static_cast<uint16_t*>(dst)[at] = (uint16_t)float_to_bf16_rne(acc[r][c][e]);
-          else static_cast<float*>(dst)[at] = acc[r][c][e];
-        }
+        float* dst = out + (size_t)row * N + n;
+        *dst = apply_epilogue(acc[r][c][e], dst, epilogue);
       }
     }
-  if constexpr (QKV) {
-    if (blockIdx.x == 0 && tid < BM && row0 + tid < rows) {
-      const int L = f.lens_in[row0 + tid];
-      f.lens_out[row0 + tid] = (L < 0 || L >= f.cap) ? L : L + 1;
-    }
-  }
 }
 
-template <bool KC, int BM, int BN, bool QKV = false>
+template <bool KC, int BM, int BN>
 hipError_t launch_tiled(const float* in, const float* P, float* out, int rows, int d, int h, int kv, int N,
-                        int epilogue, hipStream_t st, const QkvAppend& f = QkvAppend{}) {
+                        int epilogue, hipStream_t st) {
   constexpr size_t lds = 2 * (size_t)(BM * kAPitch + b_tile_floats<BN>(KC)) * sizeof(float);
-  auto kern = gemm_tiled_kernel<KC, BM, BN, QKV>;
+  auto kern = gemm_tiled_kernel<KC, BM, BN>;
   if (lds > 64 * 1024) {
     static bool done[64] = {};
     int dev = 0;
@@ -220,7 +184,7 @@ hipError_t launch_tiled(const float* in, const float* P, float* out, int rows, i
     }
   }
   const dim3 grid((N + BN - 1) / BN, (rows + BM - 1) / BM), block(256);
-  hipLaunchKernelGGL(kern, grid, block, lds, st, in, P, out, rows, d, h, kv, epilogue, f);
+  hipLaunchKernelGGL(kern, grid, block, lds, st, in, P, out, rows, d, h, kv, epilogue);
   return hipGetLastError();
 }
 
@@ -241,21 +205,6 @@ hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* o
   if (t64 >= 256)
     return outp ? launch_tiled<true, 64, 64>(in, P, out, rows, d, h, kv, N, epilogue, st)
                 : launch_tiled<false, 64, 64>(in, P, out, rows, d, h, kv, N, epilogue, st);
-  return hipErrorNotSupported;
-}
-
-// The fused q / K row / V row projection through the tiled kernel when it is large enough.
-hipError_t launch_gemm_tiled_qkv(const float* x, const float* P_q, const float* P_k, const float* P_v,
-                                 float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
-                                 int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
-                                 hipStream_t st) {
-  const int ntot = h * k + h_kv * (k + v);
-  if (rows < 64) return hipErrorNotSupported;
-  const QkvAppend f{P_k, P_v, K, V, lens_in, lens_out, h_kv, cap, v, is_bf16};
-  if ((k % 128) == 0 && (v % 128) == 0 && (long long)(ntot / 128) * ((rows + 127) / 128) >= 192)
-    return launch_tiled<false, 128, 128, true>(x, P_q, q, rows, d, h, k, ntot, 0, st, f);
-  if ((k % 64) == 0 && (v % 64) == 0 && (long long)(ntot / 64) * ((rows + 63) / 64) >= 256)
-    return launch_tiled<false, 64, 64, true>(x, P_q, q, rows, d, h, k, ntot, 0, st, f);
   return hipErrorNotSupported;
 }
 

@@ -2,7 +2,12 @@
 // and Section 3): q = einsum('bd,hdk->bhk'), the new K / V rows
 // einsum('bd,dk->bk') (multi-head: 'bd,hdk->bhk') and y = einsum('bhv,hdv->bd').
 // float32 in, float32 products and accumulation on the matrix cores
-// (v_mfma_f32_16x16x4_f32), float32 out.
+// (v_mfma_f32_16x16x4_f32), float32 out.  The new K / V rows are the exception: their
+// products (exact in float64) are accumulated in float64 (v_mfma_f64_16x16x4_f64) and the sum
+// is rounded once to float32, so that the value then rounded into a bf16 cache is the correctly
+// rounded projection and does not depend on the summation order (a float32 sum within an ulp
+// of a bf16 tie would round either way, and one flipped cache element moves an attention
+// output by up to a bf16 ulp of V).
 //
 // All four are one GEMM out[rows, N] = in[rows, C] . B[C, N] with B addressed
 // inside the projection tensor P [h, d, kv]:
@@ -51,10 +56,11 @@ template <int GC, int CB> struct BFrag<true, GC, CB> { float4 v[GC][CB]; };
 // discarded by the caller.  Column blocks: with C contiguous (OUT_PROJ) block j is columns
 // n0 + j*T + i; with N contiguous block j is columns n0 + CB*i + j, i = 0..T-1, so that a lane's
 // CB weights of one contraction index are adjacent in memory and arrive in one load.
-template <bool OUT_PROJ, int T, int RB, int CB>
+template <bool OUT_PROJ, int T, int RB, int CB, typename ACC = float>
 __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const float* __restrict__ P,
                                           int rows, int d, int h, int kv, int row0, int n0,
-                                          float (*red)[RB * T * CB * T]) {
+                                          ACC (*red)[RB * T * CB * T]) {
+  static_assert(sizeof(ACC) == 4 || T == 16, "float64 accumulation uses the 16x16x4 blocks");
   constexpr int TN = CB * T;
   constexpr int GC = (CB == 4) ? 2 : 4;        // chunks of contraction indices fetched together
   constexpr int CH = 256 / T;                  // contraction indices per chunk (4 per lane group)
@@ -78,14 +84,14 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
   const int nb = min(n0 + CB * i32, N - CB);
   const float* bcol = P + (size_t)(nb / kv) * head_stride + (nb % kv) + (size_t)(4 * kk) * kv;
 
-  typedef __attribute__((ext_vector_type(NACC))) float accv;
+  typedef __attribute__((ext_vector_type(NACC))) ACC accv;
   accv acc[RB][CB];
 #pragma unroll
   for (int r = 0; r < RB; ++r)
 #pragma unroll
     for (int j = 0; j < CB; ++j)
 #pragma unroll
-      for (int e = 0; e < NACC; ++e) acc[r][j][e] = 0.f;
+      for (int e = 0; e < NACC; ++e) acc[r][j][e] = ACC(0);
 
   const int nchunks = C / CH;                  // C is a multiple of 8; a last half chunk (T = 16) is handled below
   const int tail = C - nchunks * CH;           // 0 or 8 (only when T = 16)
@@ -124,7 +130,8 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
     }
   };
   auto mfma = [&](float x, float y, accv c) -> accv {
-    if constexpr (T == 32) return __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, c, 0, 0, 0);
+    if constexpr (sizeof(ACC) == 8) return __builtin_amdgcn_mfma_f64_16x16x4f64((double)x, (double)y, c, 0, 0, 0);
+    else if constexpr (T == 32) return __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, c, 0, 0, 0);
     else return __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, c, 0, 0, 0);
   };
   auto multiply = [&](const float4 (&a)[RB][GC], const bfrag& b) {
@@ -163,38 +170,40 @@ __device__ __forceinline__ void gemm_tile(const float* __restrict__ in, const fl
   }
 
   // D layout: register e of lane (i, g) is block element (8*(e/4) + 4*g + e%4, i) for the 32x32
-  // block and (4*g + e, i) for the 16x16 block; row block r adds r*T rows, column block j maps
-  // to tile columns as described above
+  // block, (4*g + e, i) for the float32 16x16 block and (4*e + g, i) for the float64 16x16 block
+  // (whose four result registers interleave the lane groups' rows); row block r adds r*T rows,
+  // column block j maps to tile columns as described above
 #pragma unroll
   for (int r = 0; r < RB; ++r)
 #pragma unroll
     for (int j = 0; j < CB; ++j)
 #pragma unroll
       for (int e = 0; e < NACC; ++e) {
-        const int trow = r * T + ((T == 32) ? (8 * (e >> 2) + 4 * kk + (e & 3)) : (4 * kk + e));
+        const int trow = r * T + ((T == 32) ? (8 * (e >> 2) + 4 * kk + (e & 3)) : sizeof(ACC) == 8 ? (4 * e + kk) : (4 * kk + e));
         const int tcol = OUT_PROJ ? j * T + i32 : CB * i32 + j;
         red[wave][trow * TN + tcol] = acc[r][j][e];
       }
   __syncthreads();
 }
 
-__device__ __forceinline__ float sum_partials(const float* red0, int e, int stride) {
-  return ((red0[e] + red0[stride + e]) + (red0[2 * stride + e] + red0[3 * stride + e])) +
-         ((red0[4 * stride + e] + red0[5 * stride + e]) + (red0[6 * stride + e] + red0[7 * stride + e]));
+template <typename ACC>
+__device__ __forceinline__ float sum_partials(const ACC* red0, int e, int stride) {
+  return (float)(((red0[e] + red0[stride + e]) + (red0[2 * stride + e] + red0[3 * stride + e])) +
+                 ((red0[4 * stride + e] + red0[5 * stride + e]) + (red0[6 * stride + e] + red0[7 * stride + e])));
 }
 
 // T = 16: 16x16 MFMA blocks (v_mfma_f32_16x16x4_f32, chunks of 16 contraction indices), the
 // ones launched; T = 32: 32x32 blocks (v_mfma_f32_32x32x2_f32, chunks of 8).  A workgroup owns
 // an (RB*T) x (CB*T) output tile.  Lane (i, kk): i = lane % T, kk = lane / T.
-template <bool OUT_PROJ, int T, int RB, int CB>
+template <bool OUT_PROJ, int T, int RB, int CB, typename ACC = float>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_mfma_kernel(const float* __restrict__ in, const float* __restrict__ P, float* out,
                          int rows, int d, int h, int kv, int epilogue) {
   constexpr int TM = RB * T, TN = CB * T;
-  __shared__ float red[NWAVES][TM * TN];
+  __shared__ ACC red[NWAVES][TM * TN];
   const int N = OUT_PROJ ? d : h * kv;
   const int row0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-  gemm_tile<OUT_PROJ, T, RB, CB>(in, P, rows, d, h, kv, row0, n0, red);
+  gemm_tile<OUT_PROJ, T, RB, CB, ACC>(in, P, rows, d, h, kv, row0, n0, red);
   for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
     const int r = e / TN, c = e % TN;
     if (row0 + r < rows && n0 + c < N) {
@@ -209,42 +218,54 @@ template <> __device__ __forceinline__ float cache_value<float>(float x) { retur
 template <> __device__ __forceinline__ uint16_t cache_value<uint16_t>(float x) { return (uint16_t)float_to_bf16_rne(x); }
 
 // The first three lines of the incremental listings in one launch: q = x . P_q to memory, the
-// new K and V rows x . P_k, x . P_v straight into row lens_in[i] of the caches (rounded to the
-// cache type), and lens_out[i] = lens_in[i] + 1.  Column tiles are numbered over q's h*k
-// columns, then K's h_kv*k, then V's h_kv*v (k and v are multiples of the tile width, so a tile
-// belongs to one of them).  A sequence at capacity keeps its cache and its length.
+// new K and V rows x . P_k, x . P_v straight into row lens_in[i] of the caches (accumulated in
+// float64, rounded once to float32 and then to the cache type), and lens_out[i] = lens_in[i] + 1.
+// Column tiles are numbered over q's h*k columns, then K's h_kv*k, then V's h_kv*v (k and v are
+// multiples of the tile width, so a tile belongs to one of them); the launch covers the tiles from
+// tile0 on (tile0 > 0: q was computed by another launch).  A K or V tile is worked off one row
+// block at a time so that its float64 partial tiles fit the same LDS as a q tile's float32 ones.
+// A sequence at capacity keeps its cache and its length.
 template <int T, int RB, int CB, typename CT>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_qkv_append_kernel(const float* __restrict__ x, const float* __restrict__ P_q,
                                const float* __restrict__ P_k, const float* __restrict__ P_v,
                                float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
                                const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
-                               int rows, int d, int h, int h_kv, int cap, int k, int v) {
+                               int rows, int d, int h, int h_kv, int cap, int k, int v, int tile0) {
   constexpr int TM = RB * T, TN = CB * T;
-  __shared__ float red[NWAVES][TM * TN];
+  __shared__ __align__(16) double red_raw[NWAVES * T * TN];       // = RB <= 2 float32 row blocks
+  static_assert(RB <= 2, "a q tile's float32 partial tiles must fit the float64 buffer");
   const int row0 = blockIdx.y * TM;
-  int n0 = blockIdx.x * TN;
+  const int ctile = blockIdx.x + tile0;
+  int n0 = ctile * TN;
   const int nq = h * k, nk = h_kv * k;
   int which = 0;                       // 0: q, 1: K row, 2: V row
   if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; }
   else if (n0 >= nq) { which = 1; n0 -= nq; }
   const int kv = which == 2 ? v : k;
-  gemm_tile<false, T, RB, CB>(x, which == 0 ? P_q : which == 1 ? P_k : P_v, rows, d, which == 0 ? h : h_kv, kv, row0, n0, red);
-  for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
-    const int r = e / TN, c = e % TN;
-    const int row = row0 + r, n = n0 + c;
-    if (row >= rows) continue;
-    const float val = sum_partials(&red[0][0], e, TM * TN);
-    if (which == 0) {
-      q[(size_t)row * nq + n] = val;
-    } else {
+  if (which == 0) {
+    float (*red)[TM * TN] = reinterpret_cast<float (*)[TM * TN]>(red_raw);
+    gemm_tile<false, T, RB, CB>(x, P_q, rows, d, h, kv, row0, n0, red);
+    for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
+      const int r = e / TN, c = e % TN;
+      if (row0 + r < rows) q[(size_t)(row0 + r) * nq + n0 + c] = sum_partials(&red[0][0], e, TM * TN);
+    }
+    return;
+  }
+  double (*red)[T * TN] = reinterpret_cast<double (*)[T * TN]>(red_raw);
+  CT* dst = which == 1 ? K : V;
+  for (int rb = 0; rb < RB && row0 + rb * T < rows; ++rb) {
+    if (rb) __syncthreads();           // the previous row block's sums have been read
+    gemm_tile<false, T, 1, CB, double>(x, which == 1 ? P_k : P_v, rows, d, h_kv, kv, row0 + rb * T, n0, red);
+    for (int e = threadIdx.x; e < T * TN; e += NWAVES * 64) {
+      const int row = row0 + rb * T + e / TN, n = n0 + e % TN;
+      if (row >= rows) continue;
       const int L = lens_in[row];
       if (L < 0 || L >= cap) continue;
-      CT* dst = which == 1 ? K : V;
-      dst[(((size_t)row * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(val);
+      dst[(((size_t)row * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(sum_partials(&red[0][0], e, T * TN));
     }
   }
-  if (blockIdx.x == 0 && threadIdx.x < TM && row0 + threadIdx.x < rows) {
+  if (ctile * TN == nq && threadIdx.x < TM && row0 + threadIdx.x < rows) {      // the first K tile of each row tile
     const int L = lens_in[row0 + threadIdx.x];
     lens_out[row0 + threadIdx.x] = (L < 0 || L >= cap) ? L : L + 1;
   }
@@ -282,18 +303,24 @@ static Tile pick_tile(long long ncols, int rows, int colmult) {
 
 hipError_t launch_project(int mode, const float* in, const float* P, float* out,
                           int rows, int d, int h, int kv, int epilogue, hipStream_t st) {
-  const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, epilogue, st);     // large GEMMs: LDS-tiled kernel
-  if (big != hipErrorNotSupported) return big;
   const bool outp = (mode == 3);
+  const bool f64 = (mode == 1 || mode == 2);        // new K / V rows: float64 accumulation, split-contraction kernel only
+  if (!f64) {
+    const hipError_t big = launch_gemm_tiled(mode, in, P, out, rows, d, h, kv, epilogue, st);     // large GEMMs: LDS-tiled kernel
+    if (big != hipErrorNotSupported) return big;
+  }
   const int N = outp ? d : h * kv;
   const dim3 block(NWAVES * 64);
-  const Tile t = pick_tile(N, rows, 0);
+  Tile t = pick_tile(N, rows, 0);
+  if (f64 && t.RB == 2 && t.CB == 4) t = Tile{1, 4};        // float64 partial tiles: at most 1024 elements in 64 KiB of LDS
   bool launched = false;
 #define MQA_PROJ(RB_, CB_)                                                                                           \
   if (!launched && t.RB == RB_ && t.CB == CB_) {                                                                     \
     const dim3 grid((N + CB_ * 16 - 1) / (CB_ * 16), (rows + RB_ * 16 - 1) / (RB_ * 16));                            \
     if (outp) hipLaunchKernelGGL((project_mfma_kernel<true, 16, RB_, CB_>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
-    else hipLaunchKernelGGL((project_mfma_kernel<false, 16, RB_, CB_>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue);     \
+    else if (!f64) hipLaunchKernelGGL((project_mfma_kernel<false, 16, RB_, CB_>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
+    else if constexpr (RB_ * CB_ <= 4)                                                                               \
+      hipLaunchKernelGGL((project_mfma_kernel<false, 16, RB_, CB_, double>), grid, block, 0, st, in, P, out, rows, d, h, kv, epilogue); \
     launched = true;                                                                                                 \
   }
   MQA_TILES(MQA_PROJ)
@@ -306,23 +333,26 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
                                      hipStream_t st) {
-  const hipError_t big = launch_gemm_tiled_qkv(x, P_q, P_k, P_v, q, K, V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v,
-                                               is_bf16, st);
-  if (big != hipErrorNotSupported) return big;
-  const int ntot = h * k + h_kv * (k + v);
+  // prompt-sized row counts: q through the LDS-tiled kernel, then only the K / V columns here
+  const hipError_t big = launch_gemm_tiled(0, x, P_q, q, rows, d, h, k, 0, st);
+  if (big != hipErrorNotSupported && big != hipSuccess) return big;
+  const bool q_done = (big == hipSuccess);
+  const int nq = h * k;
+  const int ntot = nq + h_kv * (k + v);
   // column tiles must not straddle q / K / V: the tile width divides k and v (both multiples of 16)
   int g = k, r = v;
   while (r) { const int t2 = g % r; g = r; r = t2; }
-  const Tile t = pick_tile(ntot, rows, g);
+  const Tile t = pick_tile(q_done ? ntot - nq : ntot, rows, g);
   const dim3 block(NWAVES * 64);
   bool launched = false;
 #define MQA_QKV(RB_, CB_)                                                                                            \
   if (!launched && t.RB == RB_ && t.CB == CB_) {                                                                     \
-    const dim3 grid(ntot / (CB_ * 16), (rows + RB_ * 16 - 1) / (RB_ * 16));                                          \
+    const int tile0 = q_done ? nq / (CB_ * 16) : 0;                                                                  \
+    const dim3 grid(ntot / (CB_ * 16) - tile0, (rows + RB_ * 16 - 1) / (RB_ * 16));                                  \
     if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);     \
+                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0); \
     else hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, float>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v);                   \
+                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0);            \
     launched = true;                                                                                                 \
   }
   MQA_TILES(MQA_QKV)

@@ -35,12 +35,16 @@ void layernorm_kernel(const float* __restrict__ x, float* __restrict__ y, int d,
   for (int i = threadIdx.x; i < d; i += 256) yr[i] = (xr[i] - mean) * rstd;
 }
 
-// x[row] = E[token[row]] + P[pos[row]]
+// x[row] = E[token[row]] + P[pos[row]]; indices outside the tables are clamped (they live on the
+// device, so the host cannot reject them)
 __global__ __launch_bounds__(256)
 void embed_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ pos,
-                  const float* __restrict__ E, const float* __restrict__ P, float* __restrict__ x, int d) {
-  const float* e = E + (size_t)tokens[blockIdx.x] * d;
-  const float* pp = P + (size_t)pos[blockIdx.x] * d;
+                  const float* __restrict__ E, const float* __restrict__ P, float* __restrict__ x, int d,
+                  int vocab, int max_pos) {
+  const int tok = min(max(tokens[blockIdx.x], 0), vocab - 1);
+  const int at = min(max(pos[blockIdx.x], 0), max_pos - 1);
+  const float* e = E + (size_t)tok * d;
+  const float* pp = P + (size_t)at * d;
   float* xr = x + (size_t)blockIdx.x * d;
   for (int i = threadIdx.x; i < d; i += 256) xr[i] = e[i] + pp[i];
 }
@@ -90,7 +94,7 @@ void argmax_kernel(const float* __restrict__ x, int32_t* __restrict__ out, int n
     bi = tid < 16 ? si[tid] : 0x7fffffff;
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) take_better(best, bi, __shfl_xor(best, o), __shfl_xor(bi, o));
-    if (tid == 0) out[blockIdx.x] = bi;
+    if (tid == 0) out[blockIdx.x] = bi < n ? bi : 0;      // a row with nothing comparable (all NaN or -inf): index 0
   }
 }
 
@@ -101,8 +105,8 @@ hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps
   return hipGetLastError();
 }
 hipError_t launch_embed(const int32_t* tokens, const int32_t* pos, const float* E, const float* P, float* x,
-                        int rows, int d, hipStream_t st) {
-  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(256), 0, st, tokens, pos, E, P, x, d);
+                        int rows, int d, int vocab, int max_pos, hipStream_t st) {
+  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(256), 0, st, tokens, pos, E, P, x, d, vocab, max_pos);
   return hipGetLastError();
 }
 hipError_t launch_add(float* a, const float* b, size_t n, hipStream_t st) {

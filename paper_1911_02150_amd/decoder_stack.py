@@ -66,9 +66,9 @@ class DecoderStack:
     def feed_forward(self, l: int, x: torch.Tensor) -> torch.Tensor:
         w = self.layers[l]
         hx = B.mqa_stack_layernorm(x)
-        u = B.mqa_project_qkvo(B.MQA_PROJ_KV, hx, w["W1"])
+        u = B.mqa_project_qkvo(B.MQA_PROJ_LINEAR, hx, w["W1"])
         B.mqa_stack_relu(u)
-        return B.mqa_project_qkvo(B.MQA_PROJ_KV, u, w["W2"])
+        return B.mqa_project_qkvo(B.MQA_PROJ_LINEAR, u, w["W2"])
 
     def logits(self, x: torch.Tensor) -> torch.Tensor:
         hx = B.mqa_stack_layernorm(x)
@@ -83,8 +83,8 @@ class DecoderStack:
             q = self.attention_append_fused(l, x)
             o = dec(q, self.K[l], self.V[l], self.lens[l])
             B.mqa_project_qkvo_ex(B.MQA_PROJ_O, o, w["P_o"], out=x, epilogue=B.MQA_EPI_ADD)
-            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
-            B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
+            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_LINEAR, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_LINEAR, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
         return self.logits(x)
 
     # -- a whole prompt at once (multi-query only): bulk append + fused causal attention per layer
@@ -103,8 +103,8 @@ class DecoderStack:
             B.mqa_append_kv_rows(self.K[l], self.V[l], kn, vn, self.lens[l])
             o = B.mqa_prefill_attention(q, self.K[l], self.V[l], self.lens[l])
             B.mqa_project_qkvo_ex(B.MQA_PROJ_O, o.view(b * n, self.h, self.v), w["P_o"], out=x, epilogue=B.MQA_EPI_ADD)
-            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
-            B.mqa_project_qkvo_ex(B.MQA_PROJ_KV, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
+            u = B.mqa_project_qkvo_ex(B.MQA_PROJ_LINEAR, B.mqa_stack_layernorm(x), w["W1"], epilogue=B.MQA_EPI_RELU)
+            B.mqa_project_qkvo_ex(B.MQA_PROJ_LINEAR, u, w["W2"], out=x, epilogue=B.MQA_EPI_ADD)
         last = x.view(b, n, self.d)[:, n - 1].contiguous()
         return self.logits(last)
 

@@ -50,6 +50,15 @@ def test_host_side_sizes_and_plan():
     assert m.mqa_decode_num_splits(1, 8, 64, 128, 128, m.MQA_BF16, tuning=dict(splits=9)) == 2   # at most cap/32
     assert m.mqa_decode_num_splits(4, 8, 64, 64, 64, m.MQA_BF16, tuning=dict(kernel=2)) == -2    # MFMA kernel needs k=v=128
     assert m.status_string(0) == "ok" and "workspace" in m.status_string(4)
+    # the whole plan, and exactly what the default plan of a shape uses
+    assert m.mqa_decode_plan(64, 32, 8192, 128, 128, m.MQA_BF16) == (4, 2048, 1)
+    assert m.mqa_decode_plan(512, 64, 4096, 128, 128, m.MQA_BF16) == (1, 4096, 2)
+    assert m.mqa_decode_plan(1, 8, 4096, 128, 128, m.MQA_BF16, window=1024) == (9, 128, 1)
+    assert m.mqa_decode_plan(2, 8, 64, 128, 128, m.MQA_BF16, multi_head=True)[0] == 1
+    assert m.mqa_decode_workspace_bytes_default(64, 32, 8192, 128, 128, m.MQA_BF16) == 64 * 32 * 4 * 130 * 4 + 64 * 4
+    assert m.mqa_decode_workspace_bytes_default(512, 64, 4096, 128, 128, m.MQA_BF16) == 512 * 4
+    assert m.mqa_decode_workspace_bytes_default(64, 32, 8192, 128, 128, m.MQA_BF16) <= m.mqa_decode_workspace_bytes(64, 32, 8192, 128)
+    assert m.mqa_decode_workspace_bytes_default(2, 4, 64, 128, 128, m.MQA_BF16, multi_head=True) == 8 * 4
 
 
 def test_argument_validation_without_gpu():
@@ -85,7 +94,8 @@ def test_argument_validation_without_gpu():
     prj = lib.mqa_project_qkvo
     prj.argtypes = [ctypes.c_int, vp, vp, vp] + [ctypes.c_int] * 4 + [vp]
     assert prj(0, None, A, A, 4, 64, 2, 16, None) == 1
-    assert prj(9, A, A, A, 4, 64, 2, 16, None) == 5
+    assert prj(9, A, A, A, 4, 64, 2, 16, None) == 5 and prj(5, A, A, A, 4, 64, 2, 16, None) == 5
+    assert prj(4, A, A, U, 4, 64, 0, 16, None) == 3          # LINEAR ignores h
     assert prj(0, A, A, A, 4, 60, 2, 16, None) == 2
     assert prj(3, A, A, U, 4, 64, 2, 16, None) == 3
 

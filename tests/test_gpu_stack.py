@@ -40,6 +40,10 @@ def test_stack_glue_kernels(m):
     got = m.mqa_stack_embed(torch.from_numpy(tok).to(DEV), torch.from_numpy(pos).to(DEV),
                             torch.from_numpy(E).to(DEV), torch.from_numpy(P).to(DEV)).cpu().numpy()
     assert np.array_equal(got, E[tok] + P[pos])
+    # indices outside the tables (they live on the device) are clamped into them, never followed
+    got = m.mqa_stack_embed(torch.tensor([-3, 50, 7], dtype=torch.int32, device=DEV), torch.tensor([9, -1, 2], dtype=torch.int32, device=DEV),
+                            torch.from_numpy(E).to(DEV), torch.from_numpy(P).to(DEV)).cpu().numpy()
+    assert np.array_equal(got, E[[0, 49, 7]] + P[[8, 0, 2]])
     a, b_ = g.standard_normal((5, 77), dtype=np.float32), g.standard_normal((5, 77), dtype=np.float32)
     da = torch.from_numpy(a.copy()).to(DEV)
     m.mqa_stack_add(da, torch.from_numpy(b_).to(DEV))
@@ -52,6 +56,11 @@ def test_stack_glue_kernels(m):
     z[2, 4999] = 50.0
     got = m.mqa_stack_argmax(torch.from_numpy(z).to(DEV)).cpu().numpy()
     assert np.array_equal(got, ods.greedy_token(z)) and got[0] == 10 and got[1] == 0 and got[2] == 4999
+    # a row with nothing comparable yields a valid index (0), so that the next embedding stays in its table
+    z[3, :] = np.nan
+    z[4, :] = -np.inf
+    got = m.mqa_stack_argmax(torch.from_numpy(z).to(DEV)).cpu().numpy()
+    assert got[3] == 0 and got[4] == 0 and got[0] == 10 and got[5] == ods.greedy_token(z[5:6])[0]
 
 
 def _check_rows(cache_rows, new_f32, ref_rows, exact_rows, what):
