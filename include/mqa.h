@@ -52,7 +52,9 @@ typedef enum {
   MQA_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned                   */
   MQA_ERR_WORKSPACE = 4,  /* workspace missing or smaller than required         */
   MQA_ERR_DTYPE = 5,      /* unknown mqa_dtype / mqa_proj_mode                  */
-  MQA_ERR_LAUNCH = 6      /* the HIP runtime refused a launch                   */
+  MQA_ERR_LAUNCH = 6,     /* the HIP runtime refused a launch                   */
+  MQA_ERR_SCRATCH_LIMIT = 7 /* mqa_decode_step_noalloc: the call needs more scratch
+                               memory than the library's static buffer holds    */
 } mqa_status;
 
 typedef enum {
@@ -267,6 +269,24 @@ int mqa_decode_num_splits(int b, int h, int cap, int k, int v, mqa_dtype dt, int
  * and head groups, for full (window = 0) or local attention.  Any output pointer may be NULL. */
 int mqa_decode_plan(int b, int h, int cap, int k, int v, mqa_dtype dt, int multi_head, int window,
                     const mqa_tuning* tuning, int32_t* splits, int32_t* chunk, int32_t* head_groups);
+
+/*
+ * mqa_decode_step for callers that cannot allocate or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the partial softmax
+ * states and the length schedule live in a static device buffer of MQA_NOALLOC_SCRATCH_BYTES
+ * inside the library (one copy per GPU, held until the process ends).  The call allocates and
+ * frees nothing.  Same arguments, kernels and results as mqa_decode_step with the library
+ * heuristics.  A shape whose plan needs more than the buffer (see
+ * mqa_decode_workspace_bytes_default; the partial states of a default plan stay under 4.3 MB for
+ * any shape, the length schedule adds 4 bytes per sequence) returns MQA_ERR_SCRATCH_LIMIT with
+ * nothing enqueued.
+ * Nothing in the buffer has to start at zero (every slot that is read was written by the same
+ * call), so no clearing is done.  All calls on one GPU share the buffer: calls that may overlap
+ * in time on one GPU (different streams) race and must be serialised by the caller.
+ */
+#define MQA_NOALLOC_SCRATCH_BYTES (8u << 20)
+int mqa_decode_step_noalloc(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                            int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, void* stream);
 
 /*
  * Measurement helpers: a plain streaming read (every 16-byte word of `src` is

@@ -21,7 +21,7 @@ EXPORTS = [
     "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mha_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_workspace_bytes_default", "mqa_decode_num_splits",
-    "mqa_decode_plan",
+    "mqa_decode_plan", "mqa_decode_step_noalloc",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
 ]
@@ -80,6 +80,7 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_decode_workspace_bytes_default.restype = sz
     lib.mqa_decode_num_splits.argtypes = [ci, ci, ci, ci, ci, ci, ci, tp]
     lib.mqa_decode_plan.argtypes = [ci] * 8 + [tp, vp, vp, vp]
+    lib.mqa_decode_step_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp]
     lib.mqa_stream_read.argtypes = [vp, sz, vp, vp]
     lib.mqa_stream_copy.argtypes = [vp, vp, sz, vp]
     lib.mqa_stack_layernorm.argtypes = [vp, vp, ci, ci, cf, vp]
@@ -224,6 +225,23 @@ def mha_decode_step(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=Non
     if tuning is None:
         return _decode("mha_decode_step", True, q, K, V, lens, o, scale, workspace, stream, None, False)
     return _decode("mha_decode_step_ex", True, q, K, V, lens, o, scale, workspace, stream, tuning)
+
+
+def mqa_decode_step_noalloc(q, K, V, lens, o, scale=1.0, stream=None):
+    """mqa_decode_step without a workspace argument and without any allocation: `o` must be given; the
+    partial states live in the library's static device buffer (calls on one GPU must not overlap)."""
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32), _check(o, "o", torch.float32)
+    b, h, k = q.shape
+    cap, v = V.shape[-2], V.shape[-1]
+    if (tuple(K.shape) != (b, cap, k) or tuple(V.shape) != (b, cap, v) or K.dtype != V.dtype or lens.numel() != b
+            or tuple(o.shape) != (b, h, v)):
+        raise ValueError("shape mismatch in mqa_decode_step_noalloc")
+    rc = lib.mqa_decode_step_noalloc(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, h, cap, k, v, _cache_dtype(K),
+                                     float(scale), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_decode_step_noalloc", rc)
+    return o
 
 
 def mqa_decode_step_window(q, K, V, lens, window, o=None, scale=1.0, workspace=None, stream=None):

@@ -4,7 +4,15 @@
 #include "../../include/mqa.h"
 #include "common.hpp"
 
+#include <mutex>
+
 using namespace mqa;
+
+// Scratch memory of mqa_decode_step_noalloc: partial softmax states and the length schedule of
+// one call.  One copy per GPU, held until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr size_t kScratchBytes = (size_t)MQA_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -19,6 +27,24 @@ constexpr int kTargetBlocks = 256;    // one workgroup per compute unit: measure
 #ifdef MQA_TIMELINE
 long long* g_timeline = nullptr;
 #endif
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MQA_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MQA_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MQA_OK;
+}
 
 struct Plan {
   bool use_mfma;
@@ -326,6 +352,18 @@ size_t mqa_decode_workspace_bytes_default(int b, int h, int cap, int k, int v, m
   return ((part + 15) & ~(size_t)15) + (size_t)nseq * sizeof(int32_t);      // + the schedule of the groups
 }
 
+int mqa_decode_step_noalloc(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                            int b, int h, int cap, int k, int v, mqa_dtype dt, float scale, void* stream) {
+  // validate first, so that a wrong call touches neither the device nor the stream
+  int rc = check_decode_args(q, K, V, lens, o, b, h, cap, k, v, (int)dt, true);
+  if (rc) return rc;
+  if (mqa_decode_workspace_bytes_default(b, h, cap, k, v, dt, 0) > kScratchBytes) return MQA_ERR_SCRATCH_LIMIT;
+  void* ws = nullptr;
+  rc = scratch_address(&ws);
+  if (rc) return rc;
+  return decode_impl(q, K, V, lens, o, b, h, cap, k, v, (int)dt, scale, ws, kScratchBytes, stream, nullptr, false, 3);
+}
+
 int mqa_append_kv(void* K, void* V, const float* k_new, const float* v_new, int32_t* lens,
                   int b, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream) {
   if (!K || !V || !k_new || !v_new || !lens) return MQA_ERR_NULL;
@@ -542,6 +580,7 @@ const char* mqa_status_string(int status) {
     case MQA_ERR_WORKSPACE: return "workspace missing or too small";
     case MQA_ERR_DTYPE: return "unknown dtype or mode";
     case MQA_ERR_LAUNCH: return "HIP launch failed";
+    case MQA_ERR_SCRATCH_LIMIT: return "problem needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }

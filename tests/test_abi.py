@@ -99,6 +99,13 @@ def test_argument_validation_without_gpu():
     assert prj(0, A, A, A, 4, 60, 2, 16, None) == 2
     assert prj(3, A, A, U, 4, 64, 2, 16, None) == 3
 
+    na = lib.mqa_decode_step_noalloc
+    na.argtypes = [vp] * 5 + [ctypes.c_int] * 6 + [ctypes.c_float, vp]
+    assert na(A, A, A, A, None, 2, 4, 64, 128, 128, 1, 1.0, None) == 1
+    assert na(A, A, A, A, A, 2, 4, 64, 12, 128, 1, 1.0, None) == 2
+    assert na(A, U, A, A, A, 2, 4, 64, 128, 128, 1, 1.0, None) == 3
+    assert na(A, A, A, A, A, 5_000_000, 1, 32, 128, 128, 1, 1.0, None) == 7   # the length schedule alone outgrows the static buffer
+
     rd = lib.mqa_stream_read
     rd.argtypes = [vp, ctypes.c_size_t, vp, vp]
     assert rd(A, 24, A, None) == 2 and rd(None, 32, A, None) == 1
