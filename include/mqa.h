@@ -74,9 +74,12 @@ typedef struct {
   int32_t flags;    /* MFMA kernel variants, 0 = default.  bit 0: single bf16 term for
                        q; bit 1: single bf16 term for the softmax weights (both
                        faster, less accurate); bit 2: plain instead of
-                       non-temporal cache loads; bit 3: more than 32 heads: 64
-                       heads per workgroup instead of two groups of 32;
-                       bit 4: 8 waves per workgroup;
+                       non-temporal cache loads; bit 3: more than 32 heads: head
+                       groups of 32 as separate workgroups instead of 64 heads
+                       per workgroup sharing each tile through LDS; bit 7: two
+                       bf16 terms for the weights in that 64-head form too (its
+                       default is one, normalised by the sum of the rounded
+                       weights); bit 4: 8 waves per workgroup;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;

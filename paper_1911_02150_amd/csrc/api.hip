@@ -53,7 +53,8 @@ struct Plan {
 
 // Split of the position axis.  Every range is a multiple of 32 positions; a
 // range is at least 128 (MFMA: one tile per wave) or 256 (generic) positions.
-int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_bf16, const Tuning& tn, Plan* pl) {
+int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_bf16, const Tuning& tn, Plan* pl,
+                int causal = 0) {
   // with a window a sequence attends to at most window positions, lying in at most
   // ceil(window/32)+1 tiles counted from the 32-aligned start of the window
   int cap = cap_all;
@@ -65,7 +66,7 @@ int plan_decode(int nseq, int G, int cap_all, int window, int k, int v, int is_b
   if (tn.kernel == 2 && !ok) return MQA_ERR_SHAPE;
   pl->use_mfma = ok && tn.kernel != 1;
   pl->HG = 1;
-  if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G, tn.flags) - 1) / mfma_heads_per_block(G, tn.flags);
+  if (pl->use_mfma) pl->HG = (G + mfma_heads_per_block(G, tn.flags, causal) - 1) / mfma_heads_per_block(G, tn.flags, causal);
   const int min_chunk = pl->use_mfma ? 128 : 256;
   int max_s = (cap + min_chunk - 1) / min_chunk;
   if (max_s > kMaxAutoSplits) max_s = kMaxAutoSplits;
@@ -150,7 +151,7 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   const int G = multi_head ? (causal_n > 0 ? causal_n : 1) : h;
   Plan pl;
   if (causal_n > 0) tn.splits = 1;     // rows end at different positions: one range per workgroup, no merge pass
-  rc = plan_decode(nseq, G, cap, window, k, v, dt == MQA_BF16, tn, &pl);
+  rc = plan_decode(nseq, G, cap, window, k, v, dt == MQA_BF16, tn, &pl, causal_n > 0);
   if (rc) return rc;
   if (causal_n > 0 && !pl.use_mfma) return MQA_ERR_SHAPE;       // causal rows: MFMA kernel only
   if (pl.S > 1) {

@@ -81,7 +81,7 @@ struct Tuning {
 
 // decode_mfma.hip: bf16 cache, k = v = 128; 16 or 32 heads per workgroup.
 bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap);
-int mfma_heads_per_block(int G, int flags);
+int mfma_heads_per_block(int G, int flags, int causal);
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
 // both segments in one launch (p.seg1 filled in, 32 heads per workgroup in both); p.order must be null
 hipError_t launch_decode_mfma_two(const DecodeParams& p, long long nblocks0, long long nblocks1, hipStream_t st);

@@ -46,11 +46,10 @@
 // beyond it), not its length, which lets the first tile be requested before the
 // length has arrived from memory.
 //
-// 64 heads in one wave (HB = 4, a tuning flag): the accumulators alone are 128
-// registers, so the kernel then runs one wave per SIMD with the q operands read
-// from LDS per tile.  Measured no faster than two head groups of 32 whose second
-// read of a tile is an L2 hit, unless the weights are also kept as single bf16
-// terms; not the default.
+// More than 32 heads: two head groups of 32 as separate workgroups read every tile twice (the
+// second read an L2 hit) and measured 4.5 TB/s where 32 heads reach 6.5; 64 heads in one wave
+// (128 accumulator registers, one wave per SIMD) stalls on its own dependency chains (3.8 TB/s).
+// The STAGE form below shares each tile between two teams of waves through LDS instead.
 #include "common.hpp"
 
 namespace mqa {
@@ -104,7 +103,7 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
 }
 
 #ifdef MQA_TIMELINE   // debug builds: per-wave wall-clock stamps (100 MHz counter shared by all CUs)
-#define MQA_STAMP(i) do { if (p.timeline && lane == 0) p.timeline[((size_t)blockIdx.x * NW + wave) * 8 + (i)] = wall_clock64(); } while (0)
+#define MQA_STAMP(i) do { if (p.timeline && lane == 0) p.timeline[((size_t)blockIdx.x * NW + (threadIdx.x >> 6)) * 8 + (i)] = wall_clock64(); } while (0)
 #else
 #define MQA_STAMP(i) do { } while (0)
 #endif
@@ -112,14 +111,25 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
 // TWO_SEG: one launch covers two caches over the same q and output rows (beam search: the rows
 // shared by the hypotheses of a source, then each hypothesis' own rows); workgroups from
 // p.nblocks0 on take the second segment's cache, grouping and slots.
-template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false>
-__global__ __launch_bounds__(NW * 64, HB == 4 ? 1 : 2)
+//
+// STAGE: the 64-head form.  The workgroup is two teams of four waves; team e takes heads
+// 32e .. 32e+31 and wave w of either team the tiles w, w+4, ... -- the two waves that need a
+// tile read it from LDS, where all eight waves put a round of four tiles (128 positions, 64 KiB)
+// with coalesced 16-byte loads of whole rows, one round ahead in registers.  Each byte of the
+// cache is requested from L2 once per workgroup, whatever the number of heads.
+template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false, bool STAGE = false>
+__global__ __launch_bounds__(NW * 64, STAGE ? 1 : 2)
 void decode_mfma_kernel(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  static_assert(!STAGE || (HB == 2 && NW == 8 && !TWO_SEG), "the staged form is two teams of four waves, 32 heads each");
+  constexpr int TEAMS = STAGE ? 2 : 1;
+  constexpr int NWT = NW / TEAMS;             // waves per team: they share the team's heads and split the tiles
+  constexpr int NT = NWT * 64;                // threads per team
+  constexpr int NH = 16 * HB;                 // heads handled by a team
+  const int lane = threadIdx.x & 63;
+  const int team = STAGE ? (int)(threadIdx.x >> 8) : 0;
+  const int tid = threadIdx.x - team * NT, wave = tid >> 6;      // thread and wave inside the team
   const int i16 = lane & 15, g = lane >> 4;
-  constexpr int NT = NW * 64;
-  constexpr int NH = 16 * HB;                 // heads handled by this block
 
   // workgroup -> (sequence, range, head group); consecutive work items share an XCD
   int nb = gridDim.x, bid = blockIdx.x;
@@ -150,7 +160,7 @@ void decode_mfma_kernel(DecodeParams p) {
     srange = (wid / sg.HG) % sg.S;
     seq = wid / (sg.HG * sg.S);
   }
-  const int head0 = hg * NH;
+  const int head0 = (hg * TEAMS + team) * NH;
   int begin = srange * sg.chunk;                // < cap by construction of S and chunk; moved up below for a window
 
   const u32x4* Kbase = reinterpret_cast<const u32x4*>(sg.K) + (size_t)seq * sg.cap * kRowU4;
@@ -192,6 +202,63 @@ void decode_mfma_kernel(DecodeParams p) {
       tl.vr[e] = __builtin_amdgcn_raw_buffer_load_b128(Vbuf, vlane + toff + (uint32_t)e * (4u * kRowU4 * 16u), 0, kAuxV);
   };
 
+  // STAGE: a round is 128 consecutive rows = 2048 16-byte chunks of K and as many of V; thread x
+  // of the workgroup fetches chunks x, x+512, x+1024, x+1536 of each (consecutive lanes,
+  // consecutive addresses) and stores chunk c of row r at position c ^ (r & 15) of the row's 16
+  // slots, so that neither these stores nor the operand reads (16 lanes reading one chunk column
+  // of 16 different rows) collide on LDS banks.
+  constexpr int kStageBytes = 128 * kRowU4 * 16;                  // one tensor's round: 32 KiB
+  unsigned char* stage_k = smem_raw + TEAMS * (HB * 4 * 64 * 16 * 2);
+  unsigned char* stage_v = stage_k + kStageBytes;
+  struct Staged { u32x4 k[STAGE ? 4 : 1], v[STAGE ? 4 : 1]; };
+  Staged st_a, st_b;                       // two rounds in flight: one being stored / read, one on its way
+  const uint32_t wg_tid = threadIdx.x;
+  auto stage_load = [&](Staged& st, uint32_t toff) {
+    if constexpr (STAGE) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        st.k[j] = __builtin_amdgcn_raw_buffer_load_b128(Kbuf, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxK);
+        st.v[j] = __builtin_amdgcn_raw_buffer_load_b128(Vbuf, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxV);
+      }
+    }
+  };
+  auto stage_store = [&](const Staged& st) {
+    if constexpr (STAGE) {
+      const uint32_t at = (wg_tid >> 4) * 256u + (((wg_tid & 15u) ^ ((wg_tid >> 4) & 15u)) << 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        *reinterpret_cast<u32x4*>(stage_k + at + j * 8192) = st.k[j];
+        *reinterpret_cast<u32x4*>(stage_v + at + j * 8192) = st.v[j];
+      }
+    }
+  };
+  // operand reads of the wave's tile (rows 32*wave .. +31 of the round)
+  auto stage_read_k = [&](Tile& tl) {
+    if constexpr (STAGE) {
+      const uint32_t row = 32u * wave + krow_in_tile;                       // + 16u; row & 15 = krow_in_tile
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const unsigned char* src = stage_k + row * 256u + ((((uint32_t)(4 * s4 + g)) ^ (uint32_t)krow_in_tile) << 4);
+        tl.kr[0][s4] = *reinterpret_cast<const u32x4*>(src);
+        tl.kr[1][s4] = *reinterpret_cast<const u32x4*>(src + 16 * 256);
+      }
+    }
+  };
+  auto stage_read_v = [&](Tile& tl) {
+    if constexpr (STAGE) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t r15 = 4u * e + g;                                    // (row & 15) of rows 4e+g and 4(e+4)+g
+        const unsigned char* src = stage_v + (32u * wave + r15) * 256u + ((((uint32_t)i16) ^ r15) << 4);
+        tl.vr[e] = *reinterpret_cast<const u32x4*>(src);
+        tl.vr[e + 4] = *reinterpret_cast<const u32x4*>(src + 16 * 256);
+      }
+    }
+  };
+  auto round_offset = [&](int r, bool wanted) -> uint32_t {
+    return wanted ? (uint32_t)(begin + 128 * r) * (uint32_t)(kRowU4 * 16) : kNoTile;
+  };
+
   MQA_STAMP(0);
   // q is requested first (loads return in order, and q is needed first), then the wave's
   // first K/V tile -- both before the length is known, so the start-up latencies overlap.
@@ -216,8 +283,13 @@ void decode_mfma_kernel(DecodeParams p) {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   if (p.window == 0) {
-    load_k(tb, tile_offset(wave, true));
-    load_v(tb, tile_offset(wave, true));
+    if constexpr (STAGE) {
+      stage_load(st_a, round_offset(0, true));
+      stage_load(st_b, round_offset(1, true));       // (zeros if the range has no second round)
+    } else {
+      load_k(tb, tile_offset(wave, true));
+      load_v(tb, tile_offset(wave, true));
+    }
   }
   MQA_STAMP(1);
   int L = sg.lens[seq / sg.lens_div];
@@ -227,8 +299,13 @@ void decode_mfma_kernel(DecodeParams p) {
   const int lo = window_lo(L, p.window);
   if (p.window > 0) {
     begin += window_base(L, p.window);
-    load_k(tb, tile_offset(wave, true));
-    load_v(tb, tile_offset(wave, true));
+    if constexpr (STAGE) {
+      stage_load(st_a, round_offset(0, true));
+      stage_load(st_b, round_offset(1, true));
+    } else {
+      load_k(tb, tile_offset(wave, true));
+      load_v(tb, tile_offset(wave, true));
+    }
   }
   // Causal rows (prefill of n queries per sequence): row r = query r / h, at position L - n + r / h,
   // attends to positions <= its own.  `end` is the largest such limit in this workgroup.
@@ -261,8 +338,8 @@ void decode_mfma_kernel(DecodeParams p) {
   const int ntiles = (end - begin + 31) >> 5;
 
   // ---- q -> LDS as MFMA B operands: qs[(hb*4 + s)*64 + lane] (hi), then lo
-  u32x4* qs = reinterpret_cast<u32x4*>(smem_raw);
   constexpr int QOPS = HB * 4 * 64;
+  u32x4* qs = reinterpret_cast<u32x4*>(smem_raw) + team * (2 * QOPS);
 #pragma unroll
   for (int it = 0; it < QITEMS; ++it) {
     const int idx = tid + it * NT;
@@ -278,18 +355,26 @@ void decode_mfma_kernel(DecodeParams p) {
     qs[slot] = hi;
     qs[QOPS + slot] = lo;
   }
+  stage_store(st_a);          // STAGE: round 0 of the range
   __syncthreads();
   MQA_STAMP(2);
 
-  floatx4 acc[HB][8];
+  // Single-term weights (PSPLIT = false): the weights enter the second MFMA rounded to bf16, so the
+  // sum that normalises them is taken over the same rounded values -- by one more MFMA whose A
+  // operand is all ones (every row of its result is sum_p P[p][head]) -- and a rounding error then
+  // only perturbs the weights relative to each other (2^-9 each, averaging out over the positions)
+  // instead of biasing a sharply peaked row by the rounding of its one large weight.
+  floatx4 acc[HB][8], accl[HB];
   float m_run[HB], l_run[HB];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     m_run[hb] = -INFINITY;
     l_run[hb] = 0.f;
+    accl[hb] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[hb][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
+  const u32x4 ones = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};      // bf16 1.0 in every slot
 
   // one tile: logits, online softmax, weighted sum; refills the tile's registers with tile tn
   auto process = [&](Tile& tl, int t, int tn) {
@@ -298,11 +383,7 @@ void decode_mfma_kernel(DecodeParams p) {
     const bool more = tn < ntiles;
 
     // ---- logits^T tiles: sc[u][hb][r] = logit(head 16hb+i16, position p0+16u+4r+g)
-    // (up to 32 heads the q operands stay in registers for the whole range; with 64 heads they
-    // would take 128 registers, so they are read from LDS tile by tile: the opaque copy of the
-    // pointer keeps the compiler from hoisting the reads out of the loop)
-    const u32x4* qs_t = qs;
-    if constexpr (HB == 4) asm volatile("" : "+v"(qs_t));
+    const u32x4* qs_t = qs;      // (loop invariant: the compiler keeps the q operands in registers)
     floatx4 sc[2][HB];
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) {
@@ -320,7 +401,8 @@ void decode_mfma_kernel(DecodeParams p) {
         }
       }
     }
-    load_k(tl, tile_offset(tn, more));       // K registers are free: fetch the tile that will use them next
+    if constexpr (STAGE) stage_read_v(tl);
+    else load_k(tl, tile_offset(tn, more)); // K registers are free: fetch the tile that will use them next
     if (t == wave) MQA_STAMP(3);
 
     if (__builtin_expect(tail, 0)) {   // ragged end of the range / start of a window: drop positions outside [lo, end)
@@ -358,7 +440,8 @@ void decode_mfma_kernel(DecodeParams p) {
         // a causal row may have seen nothing yet (maximum still -inf): subtract 0 instead, so that
         // its weights come out as 2^(-inf) = 0 rather than 2^(-inf + inf)
         const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - (mnew == -INFINITY ? 0.f : mnew));
-        l_run[hb] *= alpha;
+        if (PSPLIT) l_run[hb] *= alpha;
+        else accl[hb] *= alpha;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[hb][j] *= alpha;
         m_run[hb] = mnew;
@@ -371,9 +454,9 @@ void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           pe[4 * u + r] = __builtin_amdgcn_exp2f(sc[u][hb][r] - mref);
-          sum += pe[4 * u + r];
+          if (PSPLIT) sum += pe[4 * u + r];
         }
-      l_run[hb] += sum;
+      if (PSPLIT) l_run[hb] += sum;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         if (PSPLIT) {
@@ -385,6 +468,7 @@ void decode_mfma_kernel(DecodeParams p) {
           phi[hb][d] = pack_bf16(pe[2 * d], pe[2 * d + 1]);
         }
       }
+      if (!PSPLIT) accl[hb] = mfma16(ones, phi[hb], accl[hb]);
     }
 
     // ---- O^T += V^T . P^T, V transposed 8x8 inside the lane
@@ -404,20 +488,52 @@ void decode_mfma_kernel(DecodeParams p) {
         }
       }
     }
-    load_v(tl, tile_offset(tn, more));
+    if constexpr (!STAGE) load_v(tl, tile_offset(tn, more));
     if (t == wave) MQA_STAMP(4);
   };
-  for (int t = wave; t < ntiles; t += NW) process(tb, t, t + NW);
+  if constexpr (STAGE) {
+    // Round r is in LDS, round r+1 on its way in one register set, and round r+2 is requested
+    // into the other (freed by the store that put round r in place): two rounds in flight.
+    const int nrounds = (ntiles + 3) >> 2;
+    auto work = [&](int r) {
+      const int t = 4 * r + wave;
+      if (t < ntiles) {
+        stage_read_k(tb);
+        process(tb, t, ntiles);
+      }
+    };
+    auto advance = [&](const Staged& next) {
+      __syncthreads();                                // every wave has read its operands of this round
+      stage_store(next);
+      __syncthreads();                                // the next round is in place
+    };
+    for (int r = 0; r < nrounds; r += 2) {
+      stage_load(st_a, round_offset(r + 2, r + 2 < nrounds));
+      work(r);
+      if (r + 1 >= nrounds) break;
+      advance(st_b);
+      stage_load(st_b, round_offset(r + 3, r + 3 < nrounds));
+      work(r + 1);
+      if (r + 2 < nrounds) advance(st_a);
+    }
+  } else {
+    for (int t = wave; t < ntiles; t += NWT) process(tb, t, t + NWT);
+  }
   MQA_STAMP(5);
 
-  // ---- merge the NW wave states through LDS.  When one workgroup per CU is all that runs, the
+  // ---- merge a team's NWT wave states through LDS.  When one workgroup per CU is all that runs, the
   // merge buffers follow the q operands and a wave that finishes early writes its state without
   // waiting for the others; when several workgroups should share a CU the buffers re-use the
   // q region (after a barrier), which halves the LDS footprint.
-  if (p.merge_alias) __syncthreads();
-  float* so = reinterpret_cast<float*>(smem_raw + (p.merge_alias ? 0 : QOPS * 16 * 2));   // [NW][NH][kOPitch]
-  float* sm = so + NW * NH * kOPitch;                       // [NW][NH]     running maxima
-  float* sl = sm + NW * NH;                                 // [NW][NH][4]  sums, one per lane group g
+  if (!PSPLIT) {              // each of a head's four lanes holds the whole sum: a quarter each for the merge below
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) l_run[hb] = 0.25f * accl[hb][0];
+  }
+  if (p.merge_alias || STAGE) __syncthreads();
+  constexpr int kMergeFloats = NWT * NH * kOPitch + 5 * NWT * NH;                        // per team
+  float* so = reinterpret_cast<float*>(smem_raw + ((p.merge_alias || STAGE) ? 0 : QOPS * 16 * 2)) + team * kMergeFloats;   // [NWT][NH][kOPitch]
+  float* sm = so + NWT * NH * kOPitch;                      // [NWT][NH]     running maxima
+  float* sl = sm + NWT * NH;                                // [NWT][NH][4]  sums, one per lane group g
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     float* row = so + ((size_t)wave * NH + 16 * hb + i16) * kOPitch;
@@ -434,14 +550,14 @@ void decode_mfma_kernel(DecodeParams p) {
   }
   __syncthreads();
   constexpr int ITERS = NH * (kD / 4) / NT;                   // float4 outputs per thread
-  float fw[ITERS][NW], lw[ITERS][NW];
-  float4 xw[ITERS][NW];
+  float fw[ITERS][NWT], lw[ITERS][NWT];
+  float4 xw[ITERS][NWT];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {                        // all LDS reads first: one latency
     const int idx = tid + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < NWT; ++w) {
       fw[it][w] = sm[w * NH + hl];
       const float4 l4 = *reinterpret_cast<const float4*>(sl + (w * NH + hl) * 4);
       lw[it][w] = (l4.x + l4.y) + (l4.z + l4.w);
@@ -455,11 +571,11 @@ void decode_mfma_kernel(DecodeParams p) {
     if (head0 + hl >= sg.G) continue;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) M = fmaxf(M, fw[it][w]);
+    for (int w = 0; w < NWT; ++w) M = fmaxf(M, fw[it][w]);
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     float lsum = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < NWT; ++w) {
       const float f = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(fw[it][w] - M);   // (a row that saw nothing)
       const float4 x = xw[it][w];
       a.x += f * x.x; a.y += f * x.y; a.z += f * x.z; a.w += f * x.w;
@@ -482,19 +598,23 @@ void decode_mfma_kernel(DecodeParams p) {
   MQA_STAMP(6);
 }
 
-template <int HB, int NW>
+template <int HB, int NW, bool STAGE = false>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
   const size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
-  p.merge_alias = (nblocks > 256 || HB == 4) ? 1 : 0;      // more workgroups than CUs (or 64 heads): keep LDS small
-  const size_t q_bytes = (size_t)HB * 4 * 64 * 16 * 2;
-  const size_t merge_bytes = ((size_t)NW * 16 * HB * kOPitch + 5 * NW * 16 * HB) * sizeof(float);
-  const size_t lds = p.merge_alias ? (q_bytes > merge_bytes ? q_bytes : merge_bytes) : q_bytes + merge_bytes;
+  constexpr int TEAMS = STAGE ? 2 : 1;
+  constexpr int NWT = NW / TEAMS;
+  p.merge_alias = (nblocks > 256 || STAGE) ? 1 : 0;      // more workgroups than CUs: keep LDS small
+  const size_t q_bytes = (size_t)TEAMS * HB * 4 * 64 * 16 * 2;
+  const size_t merge_bytes = (size_t)TEAMS * ((size_t)NWT * 16 * HB * kOPitch + 5 * NWT * 16 * HB) * sizeof(float);
+  const size_t work_bytes = q_bytes + (STAGE ? 2 * 128 * kRowU4 * 16 : 0);     // q operands (+ one round of K and V)
+  const size_t lds = p.merge_alias ? (work_bytes > merge_bytes ? work_bytes : merge_bytes) : work_bytes + merge_bytes;
+  const size_t most = STAGE ? lds : q_bytes + merge_bytes;
   const dim3 grid((unsigned)nblocks), block(NW * 64);
   void (*kern)(DecodeParams);
   // Non-temporal loads unless the tiles are meant to be found in L2 by a second head group.
-  const bool ntl = !(flags & 4) && p.HG == 1;
-#define MQA_PICK(QS, PS) (ntl ? decode_mfma_kernel<HB, NW, QS, PS, true> : decode_mfma_kernel<HB, NW, QS, PS, false>)
+  const bool ntl = !(flags & 4) && (p.HG == 1 || STAGE);
+#define MQA_PICK(QS, PS) (ntl ? decode_mfma_kernel<HB, NW, QS, PS, true, false, STAGE> : decode_mfma_kernel<HB, NW, QS, PS, false, false, STAGE>)
   switch (flags & 3) {
     case 0: kern = MQA_PICK(true, true); break;
     case 1: kern = MQA_PICK(false, true); break;
@@ -502,12 +622,11 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
     default: kern = MQA_PICK(false, false); break;
   }
 #undef MQA_PICK
-  if (q_bytes + merge_bytes > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per device and kernel variant
+  if (most > 64 * 1024) {     // opt in to more than 64 KiB of LDS, once per device and kernel variant
     static bool done[64][8] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
     const int slot = (flags & 3) | (ntl ? 4 : 0);
-    const size_t most = HB == 4 ? merge_bytes : q_bytes + merge_bytes;     // 64 heads: always the aliased layout
     if (!done[dev][slot]) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)most);
@@ -526,7 +645,11 @@ bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap) {
   return is_bf16 && k == kD && v == kD && cap < (1 << 23);      // a sequence's cache is addressed with 31-bit byte offsets
 }
 
-int mfma_heads_per_block(int G, int flags) { return G <= 16 ? 16 : (G > 32 && (flags & 8)) ? 64 : 32; }
+// 16 or 32 heads per workgroup; more than 32 heads: the staged form with 64 heads per workgroup
+// (plain decode and local attention), or groups of 32 (causal rows, or by a tuning flag)
+int mfma_heads_per_block(int G, int flags, int causal) {
+  return G <= 16 ? 16 : (G > 32 && !(flags & 8) && !causal) ? 64 : 32;
+}
 
 hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, long long nblocks1, hipStream_t st) {
   constexpr int HB = 2, NW = 4;
@@ -558,9 +681,10 @@ hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, 
 
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
   const bool wide = (flags & 16) != 0;       // 8 waves per workgroup instead of 4
-  const int hpb = mfma_heads_per_block(p.G, flags);
+  const int hpb = mfma_heads_per_block(p.G, flags, p.causal_h > 0);
   if (hpb == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
-  if (hpb == 64) return launch_hb<4, 4>(p, flags, st);
+  // the staged form is bound by its arithmetic, not by HBM: single-term weights unless asked otherwise
+  if (hpb == 64) return launch_hb<2, 8, true>(p, (flags & 128) ? flags : (flags | 2), st);
   return wide ? launch_hb<2, 8>(p, flags, st) : launch_hb<2, 4>(p, flags, st);
 }
 

@@ -120,7 +120,12 @@ def test_ragged_large_batch_full_size(m):
     # all 512 x 64 output rows
     o_gen = m.mqa_decode_step(q, K, V, lens, tuning=dict(kernel=1))
     torch.cuda.synchronize()
-    assert bool(torch.isfinite(o_gen).all()) and float((o_gen - o).abs().max()) <= 2e-3
+    # (with 64 heads the MFMA path keeps the softmax weights as single bf16 terms: 2^-9 relative each, up to
+    # ~4e-3 on an output of a short sequence; the generic kernel is plain float32)
+    assert bool(torch.isfinite(o_gen).all()) and float((o_gen - o).abs().max()) <= 1e-2
+    o_two = m.mqa_decode_step(q, K, V, lens, tuning=dict(flags=128))        # two-term weights: float32-level agreement
+    torch.cuda.synchronize()
+    assert float((o_gen - o_two).abs().max()) <= 1e-4
     # the forced-large logits are present in the sample: some softmax rows are sharply peaked
     longest = [int(np.argmax(lens_np))]
     w = orc.mqa_decode_weights(q_np[longest], mi.bf16_bits_to_f64(K_np[longest]), lens_np[longest])[0]
