@@ -126,6 +126,32 @@ int mqa_project_append_qkv(const float* x, const float* P_q, const float* P_k, c
                            int b, int d, int h, int h_kv, int cap, int k, int v, mqa_dtype dt, void* stream);
 
 /*
+ * Encoder-decoder ("memory") attention: the one-query-against-a-memory form of the paper's
+ * Section 2.2 listing under the Section 3 rule (K, V, P_k, P_v lose the heads dimension) -- the
+ * attention kind that, with the two self-attentions, Section 4.1 converts to multi-query.  The
+ * memory M does not change while decoding, so its keys and values are projected once:
+ *   mqa_project_memory_kv: K[i,p,:] = M[i,p,:] . P_k, V[i,p,:] = M[i,p,:] . P_v for p < m
+ *     (float64 accumulation, rounded once to float32 and then to the cache type, like every new
+ *     K / V row), written straight into the caches, and lens[i] = m -- or mem_lens[i] clamped to
+ *     [0, m] when mem_lens (device, may be NULL) gives the number of valid memory rows of
+ *     sequence i (padded batches).  M [b,m,d]; h_kv = 1: P_k [d,k], P_v [d,v], K [b,cap,k],
+ *     V [b,cap,v]; h_kv = h: P_k [h,d,k], P_v [h,d,v], K [b,h,cap,k], V [b,h,cap,v].  m <= cap,
+ *     d % 8 = 0, k % 16 = 0, v % 16 = 0.  One launch, no intermediate rows in memory.
+ *   mqa_memory_decode_step: every decoding step then attends to that fixed cache: q [b,queries,h,k]
+ *     holds the projected queries of the `queries` decoder positions that share memory i at this
+ *     step (1 for greedy decoding, the beam width under beam search: all hypotheses of a source
+ *     read its memory once), o [b,queries,h,v].  It is mqa_decode_step over queries*h query heads;
+ *     same workspace rule with h replaced by queries*h.  The multi-head form with one query per
+ *     memory is mha_decode_step over the per-head caches.
+ */
+int mqa_project_memory_kv(const float* M, const float* P_k, const float* P_v, void* K, void* V,
+                          const int32_t* mem_lens, int32_t* lens, int b, int m, int d, int h_kv, int cap,
+                          int k, int v, mqa_dtype dt, void* stream);
+int mqa_memory_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int queries, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Cache append: the in-place form of the listings' tf.concat.  For every
  * sequence i with lens[i] < cap, writes k_new[i] / v_new[i] (converted to the
  * cache type, round-to-nearest-even for bf16) as position lens[i] and then

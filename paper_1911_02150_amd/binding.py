@@ -21,7 +21,7 @@ EXPORTS = [
     "mqa_decode_step_window", "mha_decode_step_window", "mqa_append_kv_rows", "mqa_prefill_attention", "mha_prefill_attention",
     "mqa_decode_step_beams", "mqa_decode_beams_workspace_bytes", "mqa_beam_reorder_kv", "mqa_decode_step_ex", "mha_decode_step_ex", "mqa_decode_partials", "mqa_decode_combine",
     "mqa_decode_workspace_bytes", "mha_decode_workspace_bytes", "mqa_decode_workspace_bytes_default", "mqa_decode_num_splits",
-    "mqa_decode_plan", "mqa_decode_step_noalloc",
+    "mqa_decode_plan", "mqa_decode_step_noalloc", "mqa_project_memory_kv", "mqa_memory_decode_step",
     "mqa_stream_read", "mqa_stream_copy", "mqa_status_string",
     "mqa_stack_layernorm", "mqa_stack_embed", "mqa_stack_add", "mqa_stack_relu", "mqa_stack_argmax",
 ]
@@ -56,6 +56,8 @@ def load_library(path: str = LIB_PATH):
     lib.mqa_project_qkvo_ex.argtypes = [ci, vp, vp, vp, ci, ci, ci, ci, ci, vp]
     lib.mqa_project_append_qkv.argtypes = [vp] * 9 + [ci] * 8 + [vp]
     lib.mqa_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+    lib.mqa_project_memory_kv.argtypes = [vp] * 7 + [ci] * 8 + [vp]
+    lib.mqa_memory_decode_step.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
     lib.mqa_decode_step.argtypes = dec
     lib.mha_decode_step.argtypes = dec
     win = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
@@ -365,6 +367,51 @@ def mqa_project_append_qkv(x, P_q, P_k, P_v, K, V, lens_in, lens_out, q=None, st
     if rc != 0:
         raise MqaError("mqa_project_append_qkv", rc)
     return q
+
+
+def mqa_project_memory_kv(M, P_k, P_v, K, V, lens, mem_lens=None, stream=None):
+    """M [b,m,d], P_k [d,k] or [h,d,k], P_v likewise, caches K/V ([b,cap,k] or [b,h,cap,k]), lens [b] int32
+    (output), mem_lens [b] int32 or None: projects the whole memory into the caches in one launch."""
+    lib = load_library()
+    for name, t in (("M", M), ("P_k", P_k), ("P_v", P_v)):
+        _check(t, name, torch.float32)
+    _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
+    if mem_lens is not None:
+        _check(mem_lens, "mem_lens", torch.int32)
+    b, m, d = M.shape
+    k, v = P_k.shape[-1], P_v.shape[-1]
+    h_kv = P_k.shape[0] if P_k.dim() == 3 else 1
+    cap = K.shape[-2]
+    kshape = (b, cap, k) if K.dim() == 3 else (b, h_kv, cap, k)
+    if (tuple(P_k.shape)[-2:] != (d, k) or tuple(P_v.shape)[-2:] != (d, v) or P_v.dim() != P_k.dim()
+            or (K.dim() == 3) != (P_k.dim() == 2) or tuple(K.shape) != kshape or tuple(V.shape) != kshape[:-1] + (v,)
+            or K.dtype != V.dtype or lens.numel() != b or (mem_lens is not None and mem_lens.numel() != b)):
+        raise ValueError("shape mismatch in mqa_project_memory_kv")
+    rc = lib.mqa_project_memory_kv(_ptr(M), _ptr(P_k), _ptr(P_v), _ptr(K), _ptr(V), _ptr(mem_lens), _ptr(lens),
+                                   b, m, d, h_kv, cap, k, v, _cache_dtype(K), _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_project_memory_kv", rc)
+
+
+def mqa_memory_decode_step(q, K, V, lens, o=None, scale=1.0, workspace=None, stream=None):
+    """q [b,queries,h,k] (the queries of the decoder positions sharing memory i), K [b,cap,k], V [b,cap,v],
+    lens [b] -> o [b,queries,h,v]."""
+    lib = load_library()
+    _check(q, "q", torch.float32), _check(K, "K"), _check(V, "V"), _check(lens, "lens", torch.int32)
+    b, nq, h, k = q.shape
+    cap, v = V.shape[-2], V.shape[-1]
+    if tuple(K.shape) != (b, cap, k) or tuple(V.shape) != (b, cap, v) or K.dtype != V.dtype or lens.numel() != b:
+        raise ValueError("shape mismatch in mqa_memory_decode_step")
+    if o is None:
+        o = torch.empty((b, nq, h, v), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _default_workspace(q.device, mqa_decode_workspace_bytes(b, nq * h, cap, v), stream)
+    rc = lib.mqa_memory_decode_step(_ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(o), b, nq, h, cap, k, v, _cache_dtype(K),
+                                    float(scale), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream(stream))
+    if rc != 0:
+        raise MqaError("mqa_memory_decode_step", rc)
+    return o
 
 
 def mqa_decode_beams_workspace_bytes(b, beam, h, cap_src, cap_own, k, v, dt):

@@ -512,9 +512,34 @@ int mqa_project_append_qkv(const float* x, const float* P_q, const float* P_k, c
       misaligned(V) || misaligned(lens_in) || misaligned(lens_out))
     return MQA_ERR_ALIGN;
   if (launch_project_qkv_append(x, P_q, P_k, P_v, q, K, V, lens_in, lens_out, b, d, h, h_kv, cap, k, v,
-                                dt == MQA_BF16, static_cast<hipStream_t>(stream)) != hipSuccess)
+                                dt == MQA_BF16, 0, static_cast<hipStream_t>(stream)) != hipSuccess)
     return MQA_ERR_LAUNCH;
   return MQA_OK;
+}
+
+int mqa_project_memory_kv(const float* M, const float* P_k, const float* P_v, void* K, void* V,
+                          const int32_t* mem_lens, int32_t* lens, int b, int m, int d, int h_kv, int cap,
+                          int k, int v, mqa_dtype dt, void* stream) {
+  if (!M || !P_k || !P_v || !K || !V || !lens) return MQA_ERR_NULL;
+  if (dt != MQA_F32 && dt != MQA_BF16) return MQA_ERR_DTYPE;
+  if (b <= 0 || m <= 0 || d <= 0 || h_kv <= 0 || cap <= 0 || k <= 0 || v <= 0 || m > cap) return MQA_ERR_SHAPE;
+  if ((d & 7) || (k & 15) || (v & 15) || (long long)b * m > (1ll << 30)) return MQA_ERR_SHAPE;
+  if (misaligned(M) || misaligned(P_k) || misaligned(P_v) || misaligned(K) || misaligned(V) || misaligned(lens) ||
+      (mem_lens && misaligned(mem_lens)))
+    return MQA_ERR_ALIGN;
+  if (launch_project_qkv_append(M, nullptr, P_k, P_v, nullptr, K, V, mem_lens, lens, b * m, d, 0, h_kv, cap, k, v,
+                                dt == MQA_BF16, m, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return MQA_ERR_LAUNCH;
+  return MQA_OK;
+}
+
+int mqa_memory_decode_step(const float* q, const void* K, const void* V, const int32_t* lens, float* o,
+                           int b, int queries, int h, int cap, int k, int v, mqa_dtype dt, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (queries <= 0 || h <= 0 || (long long)queries * h > (1 << 20)) return MQA_ERR_SHAPE;
+  // the queries x h rows of a memory are query heads over one shared K/V: the multi-query step
+  return decode_impl(q, K, V, lens, o, b, queries * h, cap, k, v, (int)dt, scale, workspace, workspace_bytes, stream,
+                     nullptr, false, 3);
 }
 
 int mqa_stream_read(const void* src, size_t bytes, float* sink, void* stream) {

@@ -112,7 +112,7 @@ hipError_t launch_gemm_tiled(int mode, const float* in, const float* P, float* o
 hipError_t launch_project_qkv_append(const float* x, const float* P_q, const float* P_k, const float* P_v,
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
-                                     hipStream_t st);
+                                     int mem_rows, hipStream_t st);
 
 // stack_kernels.hip
 hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps, hipStream_t st);

@@ -225,13 +225,17 @@ template <> __device__ __forceinline__ uint16_t cache_value<uint16_t>(float x) {
 // tile0 on (tile0 > 0: q was computed by another launch).  A K or V tile is worked off one row
 // block at a time so that its float64 partial tiles fit the same LDS as a q tile's float32 ones.
 // A sequence at capacity keeps its cache and its length.
+// mem_rows > 0 is the form for a whole memory (encoder-decoder attention: the memory M of the
+// Section 2.2 listing, projected once): input row r is row r % mem_rows of sequence r / mem_rows
+// and goes to that position of the cache; lens_in, if given, holds the number of valid memory
+// rows per sequence, and lens_out receives it clamped to [0, mem_rows] (mem_rows if not given).
 template <int T, int RB, int CB, typename CT>
 __global__ __launch_bounds__(NWAVES * 64)
 void project_qkv_append_kernel(const float* __restrict__ x, const float* __restrict__ P_q,
                                const float* __restrict__ P_k, const float* __restrict__ P_v,
                                float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
                                const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
-                               int rows, int d, int h, int h_kv, int cap, int k, int v, int tile0) {
+                               int rows, int d, int h, int h_kv, int cap, int k, int v, int tile0, int mem_rows) {
   constexpr int TM = RB * T, TN = CB * T;
   __shared__ __align__(16) double red_raw[NWAVES * T * TN];       // = RB <= 2 float32 row blocks
   static_assert(RB <= 2, "a q tile's float32 partial tiles must fit the float64 buffer");
@@ -260,14 +264,23 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
     for (int e = threadIdx.x; e < T * TN; e += NWAVES * 64) {
       const int row = row0 + rb * T + e / TN, n = n0 + e % TN;
       if (row >= rows) continue;
-      const int L = lens_in[row];
+      const int seq = mem_rows > 0 ? row / mem_rows : row;
+      const int L = mem_rows > 0 ? row - seq * mem_rows : lens_in[row];
       if (L < 0 || L >= cap) continue;
-      dst[(((size_t)row * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(sum_partials(&red[0][0], e, T * TN));
+      dst[(((size_t)seq * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(sum_partials(&red[0][0], e, T * TN));
     }
   }
   if (ctile * TN == nq && threadIdx.x < TM && row0 + threadIdx.x < rows) {      // the first K tile of each row tile
-    const int L = lens_in[row0 + threadIdx.x];
-    lens_out[row0 + threadIdx.x] = (L < 0 || L >= cap) ? L : L + 1;
+    const int row = row0 + threadIdx.x;
+    if (mem_rows > 0) {
+      if (row % mem_rows == 0) {
+        const int L = lens_in ? lens_in[row / mem_rows] : mem_rows;
+        lens_out[row / mem_rows] = L < 0 ? 0 : (L > mem_rows ? mem_rows : L);
+      }
+    } else {
+      const int L = lens_in[row];
+      lens_out[row] = (L < 0 || L >= cap) ? L : L + 1;
+    }
   }
 }
 
@@ -332,9 +345,10 @@ hipError_t launch_project(int mode, const float* in, const float* P, float* out,
 hipError_t launch_project_qkv_append(const float* x, const float* P_q, const float* P_k, const float* P_v,
                                      float* q, void* K, void* V, const int32_t* lens_in, int32_t* lens_out,
                                      int rows, int d, int h, int h_kv, int cap, int k, int v, int is_bf16,
-                                     hipStream_t st) {
+                                     int mem_rows, hipStream_t st) {
   // prompt-sized row counts: q through the LDS-tiled kernel, then only the K / V columns here
-  const hipError_t big = launch_gemm_tiled(0, x, P_q, q, rows, d, h, k, 0, st);
+  // (h = 0: no q at all, the projection of a memory)
+  const hipError_t big = h > 0 ? launch_gemm_tiled(0, x, P_q, q, rows, d, h, k, 0, st) : hipErrorNotSupported;
   if (big != hipErrorNotSupported && big != hipSuccess) return big;
   const bool q_done = (big == hipSuccess);
   const int nq = h * k;
@@ -350,9 +364,9 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
     const int tile0 = q_done ? nq / (CB_ * 16) : 0;                                                                  \
     const dim3 grid(ntot / (CB_ * 16) - tile0, (rows + RB_ * 16 - 1) / (RB_ * 16));                                  \
     if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0); \
+                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0, mem_rows); \
     else hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, float>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0);            \
+                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0, mem_rows);  \
     launched = true;                                                                                                 \
   }
   MQA_TILES(MQA_QKV)

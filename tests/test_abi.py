@@ -52,7 +52,8 @@ def test_host_side_sizes_and_plan():
     assert m.status_string(0) == "ok" and "workspace" in m.status_string(4)
     # the whole plan, and exactly what the default plan of a shape uses
     assert m.mqa_decode_plan(64, 32, 8192, 128, 128, m.MQA_BF16) == (4, 2048, 1)
-    assert m.mqa_decode_plan(512, 64, 4096, 128, 128, m.MQA_BF16) == (1, 4096, 2)
+    assert m.mqa_decode_plan(512, 64, 4096, 128, 128, m.MQA_BF16) == (1, 4096, 1)          # 64 heads per workgroup
+    assert m.mqa_decode_plan(512, 64, 4096, 128, 128, m.MQA_BF16, tuning=dict(flags=8)) == (1, 4096, 2)
     assert m.mqa_decode_plan(1, 8, 4096, 128, 128, m.MQA_BF16, window=1024) == (9, 128, 1)
     assert m.mqa_decode_plan(2, 8, 64, 128, 128, m.MQA_BF16, multi_head=True)[0] == 1
     assert m.mqa_decode_workspace_bytes_default(64, 32, 8192, 128, 128, m.MQA_BF16) == 64 * 32 * 4 * 130 * 4 + 64 * 4
@@ -105,6 +106,17 @@ def test_argument_validation_without_gpu():
     assert na(A, A, A, A, A, 2, 4, 64, 12, 128, 1, 1.0, None) == 2
     assert na(A, U, A, A, A, 2, 4, 64, 128, 128, 1, 1.0, None) == 3
     assert na(A, A, A, A, A, 5_000_000, 1, 32, 128, 128, 1, 1.0, None) == 7   # the length schedule alone outgrows the static buffer
+
+    mem = lib.mqa_project_memory_kv
+    mem.argtypes = [vp] * 7 + [ctypes.c_int] * 8 + [vp]
+    assert mem(A, A, A, A, A, None, A, 2, 64, 128, 1, 64, 128, 128, 1, None) != 1      # mem_lens may be NULL
+    assert mem(A, A, None, A, A, None, A, 2, 64, 128, 1, 64, 128, 128, 1, None) == 1
+    assert mem(A, A, A, A, A, None, A, 2, 65, 128, 1, 64, 128, 128, 1, None) == 2      # memory longer than the cache
+    assert mem(A, A, A, A, A, U, A, 2, 64, 128, 1, 64, 128, 128, 1, None) == 3
+    md = lib.mqa_memory_decode_step
+    md.argtypes = [vp] * 5 + [ctypes.c_int] * 7 + [ctypes.c_float, vp, ctypes.c_size_t, vp]
+    assert md(A, A, A, A, A, 2, 0, 8, 64, 128, 128, 1, 1.0, None, 0, None) == 2
+    assert md(A, A, None, A, A, 2, 4, 8, 64, 128, 128, 1, 1.0, None, 0, None) == 1
 
     rd = lib.mqa_stream_read
     rd.argtypes = [vp, ctypes.c_size_t, vp, vp]
