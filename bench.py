@@ -301,7 +301,7 @@ def ragged_workload(m, mi, dev, steps=30, warmup=5):
     Ks.append(Ks[0].clone())
     Vs.append(Vs[0].clone())
     ws = torch.empty(m.mqa_decode_workspace_bytes(b, h, cap, 128), dtype=torch.uint8, device=dev)
-    ms = time_region(lambda i: m.mqa_decode_step(q, Ks[i % 2], Vs[i % 2], lens, o=o, workspace=ws), steps, warmup, settle_s=0.1)
+    ms = time_region(lambda i: m.mqa_decode_step(q, Ks[i % 2], Vs[i % 2], lens, o=o, workspace=ws), steps, warmup)
     kvb = int(lens_np.sum()) * 512
     qob = 2 * b * h * 128 * 4
     return {"step_us": ms * 1e3, "kv_bytes": kvb, "kv_GBps": kvb / (ms * 1e-3) / 1e9,

@@ -208,12 +208,13 @@ void decode_mfma_kernel(DecodeParams p) {
   // slots, so that neither these stores nor the operand reads (16 lanes reading one chunk column
   // of 16 different rows) collide on LDS banks.
   constexpr int kStageBytes = 128 * kRowU4 * 16;                  // one tensor's round: 32 KiB
-  unsigned char* stage_k = smem_raw + TEAMS * (HB * 4 * 64 * 16 * 2);
-  unsigned char* stage_v = stage_k + kStageBytes;
+  unsigned char* stage0 = smem_raw + TEAMS * (HB * 4 * 64 * 16 * 2);     // two buffers of (K round, V round)
+  unsigned char* stage_k = stage0;                                        // the buffer being read
+  unsigned char* stage_v = stage0 + kStageBytes;
   struct Staged { u32x4 k[STAGE ? 4 : 1], v[STAGE ? 4 : 1]; };
-  Staged st_a, st_b;                       // two rounds in flight: one being stored / read, one on its way
+  Staged st;                               // the round after the one in the other LDS buffer, on its way
   const uint32_t wg_tid = threadIdx.x;
-  auto stage_load = [&](Staged& st, uint32_t toff) {
+  auto stage_load = [&](uint32_t toff) {
     if constexpr (STAGE) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -222,13 +223,13 @@ void decode_mfma_kernel(DecodeParams p) {
       }
     }
   };
-  auto stage_store = [&](const Staged& st) {
+  auto stage_store = [&](int buf) {
     if constexpr (STAGE) {
-      const uint32_t at = (wg_tid >> 4) * 256u + (((wg_tid & 15u) ^ ((wg_tid >> 4) & 15u)) << 4);
+      unsigned char* dst = stage0 + buf * (2 * kStageBytes) + (wg_tid >> 4) * 256u + (((wg_tid & 15u) ^ ((wg_tid >> 4) & 15u)) << 4);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        *reinterpret_cast<u32x4*>(stage_k + at + j * 8192) = st.k[j];
-        *reinterpret_cast<u32x4*>(stage_v + at + j * 8192) = st.v[j];
+        *reinterpret_cast<u32x4*>(dst + j * 8192) = st.k[j];
+        *reinterpret_cast<u32x4*>(dst + kStageBytes + j * 8192) = st.v[j];
       }
     }
   };
@@ -284,8 +285,7 @@ void decode_mfma_kernel(DecodeParams p) {
   asm volatile("" ::: "memory");
   if (p.window == 0) {
     if constexpr (STAGE) {
-      stage_load(st_a, round_offset(0, true));
-      stage_load(st_b, round_offset(1, true));       // (zeros if the range has no second round)
+      stage_load(round_offset(0, true));
     } else {
       load_k(tb, tile_offset(wave, true));
       load_v(tb, tile_offset(wave, true));
@@ -300,8 +300,7 @@ void decode_mfma_kernel(DecodeParams p) {
   if (p.window > 0) {
     begin += window_base(L, p.window);
     if constexpr (STAGE) {
-      stage_load(st_a, round_offset(0, true));
-      stage_load(st_b, round_offset(1, true));
+      stage_load(round_offset(0, true));
     } else {
       load_k(tb, tile_offset(wave, true));
       load_v(tb, tile_offset(wave, true));
@@ -355,7 +354,8 @@ void decode_mfma_kernel(DecodeParams p) {
     qs[slot] = hi;
     qs[QOPS + slot] = lo;
   }
-  stage_store(st_a);          // STAGE: round 0 of the range
+  stage_store(0);             // STAGE: round 0 of the range into the first buffer ...
+  stage_load(round_offset(1, true));      // ... and round 1 requested (zeros if there is none)
   __syncthreads();
   MQA_STAMP(2);
 
@@ -492,29 +492,24 @@ void decode_mfma_kernel(DecodeParams p) {
     if (t == wave) MQA_STAMP(4);
   };
   if constexpr (STAGE) {
-    // Round r is in LDS, round r+1 on its way in one register set, and round r+2 is requested
-    // into the other (freed by the store that put round r in place): two rounds in flight.
+    // Round r is read from LDS buffer r & 1 while round r+1 arrives in registers; it is stored into
+    // the other buffer (last read in round r-1, which the barrier at the end of that round closed)
+    // as soon as this wave is done with its tile, round r+2 is requested into the freed registers,
+    // and one barrier ends the round.
     const int nrounds = (ntiles + 3) >> 2;
-    auto work = [&](int r) {
+    for (int r = 0; r < nrounds; ++r) {
+      stage_k = stage0 + (r & 1) * (2 * kStageBytes);
+      stage_v = stage_k + kStageBytes;
       const int t = 4 * r + wave;
       if (t < ntiles) {
         stage_read_k(tb);
         process(tb, t, ntiles);
       }
-    };
-    auto advance = [&](const Staged& next) {
-      __syncthreads();                                // every wave has read its operands of this round
-      stage_store(next);
-      __syncthreads();                                // the next round is in place
-    };
-    for (int r = 0; r < nrounds; r += 2) {
-      stage_load(st_a, round_offset(r + 2, r + 2 < nrounds));
-      work(r);
-      if (r + 1 >= nrounds) break;
-      advance(st_b);
-      stage_load(st_b, round_offset(r + 3, r + 3 < nrounds));
-      work(r + 1);
-      if (r + 2 < nrounds) advance(st_a);
+      if (r + 1 < nrounds) {
+        stage_store((r + 1) & 1);
+        stage_load(round_offset(r + 2, r + 2 < nrounds));
+        __syncthreads();
+      }
     }
   } else {
     for (int t = wave; t < ntiles; t += NWT) process(tb, t, t + NWT);
@@ -607,7 +602,7 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   p.merge_alias = (nblocks > 256 || STAGE) ? 1 : 0;      // more workgroups than CUs: keep LDS small
   const size_t q_bytes = (size_t)TEAMS * HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = (size_t)TEAMS * ((size_t)NWT * 16 * HB * kOPitch + 5 * NWT * 16 * HB) * sizeof(float);
-  const size_t work_bytes = q_bytes + (STAGE ? 2 * 128 * kRowU4 * 16 : 0);     // q operands (+ one round of K and V)
+  const size_t work_bytes = q_bytes + (STAGE ? 4 * 128 * kRowU4 * 16 : 0);     // q operands (+ two rounds of K and V)
   const size_t lds = p.merge_alias ? (work_bytes > merge_bytes ? work_bytes : merge_bytes) : work_bytes + merge_bytes;
   const size_t most = STAGE ? lds : q_bytes + merge_bytes;
   const dim3 grid((unsigned)nblocks), block(NW * 64);

@@ -157,18 +157,31 @@ __global__ __launch_bounds__(1024)
 void length_order_kernel(const int32_t* lens, int lens_div, int nseq, int cap, int32_t* order) {
   __shared__ int count[1024];
   __shared__ int start[1024];
-  const int tid = threadIdx.x;
-  count[tid] = 0;
-  __syncthreads();
+  __shared__ int cmin[16], cmax[16];
+  __shared__ int wave_total[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float per_pos = 1023.0f / (float)cap;
-  auto cls = [&](int i) {
-    int L = lens[i / lens_div];
+  auto cls_of = [&](int L) {
     L = L < 0 ? 0 : (L > cap ? cap : L);
     return 1023 - min(1023, (int)((float)L * per_pos));      // class 0 holds the longest
   };
+  // a thread's first kKeep groups stay in registers (every group, up to 4096 of them): the lengths are
+  // read from memory once, all loads in flight together, instead of once per pass
+  constexpr int kKeep = 4;
+  int mine[kKeep];
+#pragma unroll
+  for (int u = 0; u < kKeep; ++u) {
+    const int i = tid + 1024 * u;
+    mine[u] = i < nseq ? cls_of(lens[i / lens_div]) : -1;
+  }
+  auto cls = [&](int i) {                                  // group i = tid + 1024 u of this thread
+    const int u = i >> 10;
+    int c = u == 0 ? mine[0] : u == 1 ? mine[1] : u == 2 ? mine[2] : u == 3 ? mine[3] : -1;
+    return c >= 0 ? c : cls_of(lens[i / lens_div]);
+  };
+  count[tid] = 0;
   // all groups in one class (equal lengths, the common case): keep the given order and spare the
   // atomics, which would all hit one counter
-  __shared__ int cmin[16], cmax[16];
   int lo = 1023, hi = 0;
   for (int i = tid; i < nseq; i += 1024) {
     const int c = cls(i);
@@ -180,7 +193,7 @@ void length_order_kernel(const int32_t* lens, int lens_div, int nseq, int cap, i
     lo = min(lo, __shfl_xor(lo, off));
     hi = max(hi, __shfl_xor(hi, off));
   }
-  if ((tid & 63) == 0) { cmin[tid >> 6] = lo; cmax[tid >> 6] = hi; }
+  if (lane == 0) { cmin[wave] = lo; cmax[wave] = hi; }
   __syncthreads();
   for (int w = 0; w < 16; ++w) { lo = min(lo, cmin[w]); hi = max(hi, cmax[w]); }
   if (lo >= hi) {
@@ -190,8 +203,6 @@ void length_order_kernel(const int32_t* lens, int lens_div, int nseq, int cap, i
   for (int i = tid; i < nseq; i += 1024) atomicAdd(&count[cls(i)], 1);
   __syncthreads();
   // exclusive prefix sum over the classes: inside each wave with shuffles, then over the 16 wave totals
-  __shared__ int wave_total[16];
-  const int lane = tid & 63, wave = tid >> 6;
   const int x = count[tid];
   int incl = x;
 #pragma unroll
