@@ -79,7 +79,10 @@ typedef struct {
                        per workgroup sharing each tile through LDS; bit 7: two
                        bf16 terms for the weights in that 64-head form too (its
                        default is one, normalised by the sum of the rounded
-                       weights); bit 4: 8 waves per workgroup;
+                       weights); bit 4: 8 waves per workgroup; bit 8: 2 waves per
+                       workgroup for up to 16 heads (default: only for ranges of
+                       at most 128 positions in launches of 512 workgroups or
+                       more), bit 9: never 2;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;

@@ -677,6 +677,11 @@ hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, 
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) {
   const bool wide = (flags & 16) != 0;       // 8 waves per workgroup instead of 4
   const int hpb = mfma_heads_per_block(p.G, flags, p.causal_h > 0);
+  // Short ranges (at most one tile per wave of a 4-wave workgroup) in a launch of many workgroups: 2 waves
+  // per workgroup, so that more of them are resident and less of each one's time is the merge of its waves.
+  const long long nblocks = (long long)p.nseq * p.S * p.HG;
+  const bool narrow = (flags & 256) || (!(flags & 512) && !wide && p.chunk <= 128 && nblocks >= 512);
+  if (hpb == 16 && narrow) return launch_hb<1, 2>(p, flags, st);
   if (hpb == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
   // the staged form is bound by its arithmetic, not by HBM: single-term weights unless asked otherwise
   if (hpb == 64) return launch_hb<2, 8, true>(p, (flags & 128) ? flags : (flags | 2), st);
