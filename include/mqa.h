@@ -82,7 +82,9 @@ typedef struct {
                        weights); bit 4: 8 waves per workgroup; bit 8: 2 waves per
                        workgroup for up to 16 heads (default: only for ranges of
                        at most 128 positions in launches of 512 workgroups or
-                       more), bit 9: never 2;
+                       more), bit 9: never 2; bit 10: one workgroup per sequence even
+                       where the 64-head form would keep one workgroup per
+                       compute unit going over several ranked sequences;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;

@@ -44,6 +44,8 @@ struct DecodeParams {
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
   int merge_alias;       // MFMA kernel: 1 = the wave-merge buffers re-use the q operands' LDS
+  int persist;           // MFMA kernel, 64-head form with `order`: > 0 = that many workgroups (the grid) each take
+                         // several ranked sequences in turn instead of one workgroup per sequence
   float qscale;          // scale * log2(e): logits are kept in the log2 domain
   // MFMA kernel, two-segment launches only: workgroups [nblocks0, grid) work on seg1 instead of
   // the fields above (same q, o and partial-state rows)

@@ -144,7 +144,17 @@ void decode_mfma_kernel(DecodeParams p) {
     }
   }
   int hg, srange, seq;
-  if (p.order) {
+  // Persistent form (64-head kernel over a ranked ragged batch, one range and one head group per
+  // sequence): the grid is one workgroup per compute unit and workgroup j takes the sequences ranked
+  // j, 2N-1-j, 2N+j, ... (N workgroups; back and forth over the ranking, so that a long first
+  // sequence is followed by a short second one), requesting the next sequence's q and first rows
+  // while the current one's last rows are still being worked on.
+  const bool persist = STAGE && p.persist > 0;
+  int pass = 0;
+  if (persist) {
+    hg = srange = 0;
+    seq = p.order[bid];
+  } else if (p.order) {
     // Longest-first schedule: workgroups are dispatched in index order, round-robin over the
     // 8 XCDs, so XCD x takes the sequences ranked x, x+8, ... by length, longest first, and all
     // work items of a sequence stay on that XCD.
@@ -162,9 +172,6 @@ void decode_mfma_kernel(DecodeParams p) {
   }
   const int head0 = (hg * TEAMS + team) * NH;
   int begin = srange * sg.chunk;                // < cap by construction of S and chunk; moved up below for a window
-
-  const u32x4* Kbase = reinterpret_cast<const u32x4*>(sg.K) + (size_t)seq * sg.cap * kRowU4;
-  const u32x4* Vbase = reinterpret_cast<const u32x4*>(sg.V) + (size_t)seq * sg.cap * kRowU4;
   const int krow_in_tile = 4 * (i16 & 3) + (i16 >> 2);
 
   // Tile loads go through buffer descriptors of the sequence's K and V (base, cap rows of 256 B):
@@ -177,10 +184,18 @@ void decode_mfma_kernel(DecodeParams p) {
   // slower: the memory pipeline accepts the extra requests no sooner.)
   struct Tile { u32x4 kr[2][4]; u32x4 vr[8]; };
   Tile tb;
-  const __amdgpu_buffer_rsrc_t Kbuf = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u32x4*>(Kbase), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
-  const __amdgpu_buffer_rsrc_t Vbuf = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<u32x4*>(Vbase), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
+  // (the sequence index is the same in every lane; saying so keeps the descriptors in scalar registers)
+  auto k_rows_of = [&](int s) {
+    const size_t su = (size_t)__builtin_amdgcn_readfirstlane(s);
+    return __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u32x4*>(reinterpret_cast<const u32x4*>(sg.K) + su * sg.cap * kRowU4), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
+  };
+  auto v_rows_of = [&](int s) {
+    const size_t su = (size_t)__builtin_amdgcn_readfirstlane(s);
+    return __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<u32x4*>(reinterpret_cast<const u32x4*>(sg.V) + su * sg.cap * kRowU4), 0, sg.cap * (kRowU4 * 16), kBufferWord3);
+  };
+  __amdgpu_buffer_rsrc_t Kbuf = k_rows_of(seq), Vbuf = v_rows_of(seq);
   const uint32_t klane = (uint32_t)(krow_in_tile * kRowU4 + g) * 16u;      // row krow_in_tile, 16-byte chunk g
   const uint32_t vlane = (uint32_t)(g * kRowU4 + i16) * 16u;               // row g, 16-byte chunk i16
   constexpr int kAuxK = NTL ? 2 : 0, kAuxV = NTL ? 2 : 0;                   // non-temporal hint
@@ -214,15 +229,16 @@ void decode_mfma_kernel(DecodeParams p) {
   struct Staged { u32x4 k[STAGE ? 4 : 1], v[STAGE ? 4 : 1]; };
   Staged st;                               // the round after the one in the other LDS buffer, on its way
   const uint32_t wg_tid = threadIdx.x;
-  auto stage_load = [&](uint32_t toff) {
+  auto stage_load_from = [&](__amdgpu_buffer_rsrc_t kb, __amdgpu_buffer_rsrc_t vb, uint32_t toff) {
     if constexpr (STAGE) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        st.k[j] = __builtin_amdgcn_raw_buffer_load_b128(Kbuf, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxK);
-        st.v[j] = __builtin_amdgcn_raw_buffer_load_b128(Vbuf, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxV);
+        st.k[j] = __builtin_amdgcn_raw_buffer_load_b128(kb, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxK);
+        st.v[j] = __builtin_amdgcn_raw_buffer_load_b128(vb, wg_tid * 16u + toff + (uint32_t)j * 8192u, 0, kAuxV);
       }
     }
   };
+  auto stage_load = [&](uint32_t toff) { stage_load_from(Kbuf, Vbuf, toff); };
   auto stage_store = [&](int buf) {
     if constexpr (STAGE) {
       unsigned char* dst = stage0 + buf * (2 * kStageBytes) + (wg_tid >> 4) * 256u + (((wg_tid & 15u) ^ ((wg_tid >> 4) & 15u)) << 4);
@@ -260,39 +276,63 @@ void decode_mfma_kernel(DecodeParams p) {
     return wanted ? (uint32_t)(begin + 128 * r) * (uint32_t)(kRowU4 * 16) : kNoTile;
   };
 
-  MQA_STAMP(0);
   // q is requested first (loads return in order, and q is needed first), then the wave's
   // first K/V tile -- both before the length is known, so the start-up latencies overlap.
   // (Rows are in bounds for any length.)
   constexpr int QITEMS = (NH * 16 + NT - 1) / NT;        // (head, 16-byte chunk) items per thread
   float4 qa[QITEMS], qb[QITEMS];
+  // In the persistent form everything below runs once per sequence, so the compiler would compute
+  // the per-thread addresses of the start-up and merge code once, before the first sequence, and
+  // hold them in registers through the rounds, where registers are short.  An opaque copy of the
+  // thread index keeps those computations where they are used.
+  auto here = [&](int x) {
+    if constexpr (STAGE) asm volatile("" : "+v"(x));
+    return x;
+  };
+  auto load_q = [&](int s, bool wanted) {
+    const int tid_q = here(tid);
 #pragma unroll
-  for (int it = 0; it < QITEMS; ++it) {
-    const int idx = tid + it * NT;
-    const int hl = idx >> 4, c = idx & 15;               // head in block, 8-float chunk of the row
-    qa[it] = qb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (idx < NH * 16 && head0 + hl < sg.G) {
-      const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)seq * sg.G + head0 + hl) * kD + c * 8);
-      qa[it] = src[0];
-      qb[it] = src[1];
+    for (int it = 0; it < QITEMS; ++it) {
+      const int idx = tid_q + it * NT;
+      const int hl = idx >> 4, c = idx & 15;               // head in block, 8-float chunk of the row
+      qa[it] = qb[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (wanted && idx < NH * 16 && head0 + hl < sg.G) {
+        const float4* src = reinterpret_cast<const float4*>(p.q + ((size_t)s * sg.G + head0 + hl) * kD + c * 8);
+        qa[it] = src[0];
+        qb[it] = src[1];
+      }
     }
-  }
-  // All waves of the workgroup put their q requests into the CU's memory queue before any of
-  // them queues its 16 KiB of K/V (plain s_barrier: no wait for the data), so q is not stuck
-  // behind the other waves' tiles and can be converted while the tiles stream in.
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  if (p.window == 0) {
-    if constexpr (STAGE) {
-      stage_load(round_offset(0, true));
-    } else {
-      load_k(tb, tile_offset(wave, true));
-      load_v(tb, tile_offset(wave, true));
+  };
+  int seq_next = -1, L_next = 0;
+  bool prefetched = false;    // persistent form: q, the length and the first round were requested during the previous sequence
+  for (;;) {                  // one turn per sequence: a single one unless persistent
+  MQA_STAMP(0);
+  const bool started = prefetched;
+  prefetched = false;
+  if (!started) {
+    load_q(seq, true);
+    // All waves of the workgroup put their q requests into the CU's memory queue before any of
+    // them queues its 16 KiB of K/V (plain s_barrier: no wait for the data), so q is not stuck
+    // behind the other waves' tiles and can be converted while the tiles stream in.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (p.window == 0) {
+      if constexpr (STAGE) {
+        stage_load(round_offset(0, true));
+      } else {
+        load_k(tb, tile_offset(wave, true));
+        load_v(tb, tile_offset(wave, true));
+      }
     }
   }
   MQA_STAMP(1);
-  int L = sg.lens[seq / sg.lens_div];
+  int L = started ? L_next : sg.lens[seq / sg.lens_div];
+  if (persist) {              // which sequence comes after this one: asked for now, needed a round before this one ends
+    ++pass;
+    const int rank = pass * p.persist + ((pass & 1) ? p.persist - 1 - bid : bid);
+    seq_next = rank < p.nseq ? p.order[rank] : -1;
+  }
   L = L < 0 ? 0 : (L > sg.cap ? sg.cap : L);
   // Local attention (the paper's Section 4.1 variant): only positions [lo, L) count; the ranges
   // then start at the 32-aligned position below lo, which is known only now.
@@ -308,7 +348,7 @@ void decode_mfma_kernel(DecodeParams p) {
   }
   // Causal rows (prefill of n queries per sequence): row r = query r / h, at position L - n + r / h,
   // attends to positions <= its own.  `end` is the largest such limit in this workgroup.
-  const int causal_h = p.causal_h;
+  const int causal_h = STAGE ? 0 : p.causal_h;      // (the 64-head form is never used for causal rows)
   const int nq = causal_h > 0 ? sg.G / causal_h : 1;
   int lim[HB];                                   // first position the lane's row (per head block) must NOT see
   int lim_min = L, lim_max = L;
@@ -325,23 +365,41 @@ void decode_mfma_kernel(DecodeParams p) {
   const int mask_from = min(end, lim_min);        // tiles reaching beyond this position need masking
   if (end <= begin) {
     if (p.PS == 0) {          // empty sequence: zero output rows
-      for (int idx = tid; idx < NH * (kD / 4); idx += NT) {
+      for (int idx = here(tid); idx < NH * (kD / 4); idx += NT) {
         int hl = idx / (kD / 4), c4 = idx % (kD / 4);
         if (head0 + hl < sg.G)
           reinterpret_cast<float4*>(p.o + ((size_t)seq * sg.G + head0 + hl) * kD)[c4] =
               make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
-    return;                   // ranges past the length write nothing; the combine pass skips them
+    // ranges past the length write nothing; the combine pass skips them
+    if (!persist || seq_next < 0) return;
+    seq = seq_next;
+    Kbuf = k_rows_of(seq);
+    Vbuf = v_rows_of(seq);
+    continue;
   }
   const int ntiles = (end - begin + 31) >> 5;
+  const int nrounds = (ntiles + 3) >> 2;           // (64-head form)
+  // Load slot s of a sequence fetches its round s; the slot after the last round is used, in the
+  // persistent form, for the next sequence's first round (its q and length are requested when the
+  // rounds are done and the accumulators are about to leave the registers).
+  auto issue_slot = [&](int s) {
+    if (s < nrounds) {
+      stage_load(round_offset(s, true));
+    } else if (s == nrounds && persist && seq_next >= 0) {
+      stage_load_from(k_rows_of(seq_next), v_rows_of(seq_next), 0u);
+      prefetched = true;
+    }
+  };
 
   // ---- q -> LDS as MFMA B operands: qs[(hb*4 + s)*64 + lane] (hi), then lo
   constexpr int QOPS = HB * 4 * 64;
   u32x4* qs = reinterpret_cast<u32x4*>(smem_raw) + team * (2 * QOPS);
+  const int tid_s = here(tid);
 #pragma unroll
   for (int it = 0; it < QITEMS; ++it) {
-    const int idx = tid + it * NT;
+    const int idx = tid_s + it * NT;
     if (idx >= NH * 16) break;
     const int hl = idx >> 4, c = idx & 15;
     const int s4 = c >> 2, gg = c & 3;              // chunk c = 4s + g
@@ -355,7 +413,7 @@ void decode_mfma_kernel(DecodeParams p) {
     qs[QOPS + slot] = lo;
   }
   stage_store(0);             // STAGE: round 0 of the range into the first buffer ...
-  stage_load(round_offset(1, true));      // ... and round 1 requested (zeros if there is none)
+  if constexpr (STAGE) issue_slot(1);     // ... and round 1 requested
   __syncthreads();
   MQA_STAMP(2);
 
@@ -496,7 +554,6 @@ void decode_mfma_kernel(DecodeParams p) {
     // the other buffer (last read in round r-1, which the barrier at the end of that round closed)
     // as soon as this wave is done with its tile, round r+2 is requested into the freed registers,
     // and one barrier ends the round.
-    const int nrounds = (ntiles + 3) >> 2;
     for (int r = 0; r < nrounds; ++r) {
       stage_k = stage0 + (r & 1) * (2 * kStageBytes);
       stage_v = stage_k + kStageBytes;
@@ -507,7 +564,7 @@ void decode_mfma_kernel(DecodeParams p) {
       }
       if (r + 1 < nrounds) {
         stage_store((r + 1) & 1);
-        stage_load(round_offset(r + 2, r + 2 < nrounds));
+        issue_slot(r + 2);
         __syncthreads();
       }
     }
@@ -515,6 +572,10 @@ void decode_mfma_kernel(DecodeParams p) {
     for (int t = wave; t < ntiles; t += NWT) process(tb, t, t + NWT);
   }
   MQA_STAMP(5);
+  if constexpr (STAGE) {      // (assigned either way, so that no old value has to be carried through the rounds)
+    load_q(seq_next, prefetched);
+    L_next = prefetched ? sg.lens[seq_next / sg.lens_div] : 0;
+  }
 
   // ---- merge a team's NWT wave states through LDS.  When one workgroup per CU is all that runs, the
   // merge buffers follow the q operands and a wave that finishes early writes its state without
@@ -529,27 +590,29 @@ void decode_mfma_kernel(DecodeParams p) {
   float* so = reinterpret_cast<float*>(smem_raw + ((p.merge_alias || STAGE) ? 0 : QOPS * 16 * 2)) + team * kMergeFloats;   // [NWT][NH][kOPitch]
   float* sm = so + NWT * NH * kOPitch;                      // [NWT][NH]     running maxima
   float* sl = sm + NWT * NH;                                // [NWT][NH][4]  sums, one per lane group g
+  const int lane_m = here(lane), i16m = lane_m & 15, gm = lane_m >> 4;
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
-    float* row = so + ((size_t)wave * NH + 16 * hb + i16) * kOPitch;
+    float* row = so + ((size_t)wave * NH + 16 * hb + i16m) * kOPitch;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float4 lo4 = make_float4(acc[hb][0][r], acc[hb][1][r], acc[hb][2][r], acc[hb][3][r]);
       float4 hi4 = make_float4(acc[hb][4][r], acc[hb][5][r], acc[hb][6][r], acc[hb][7][r]);
-      float4* dst = reinterpret_cast<float4*>(row + 8 * (4 * g + r));
+      float4* dst = reinterpret_cast<float4*>(row + 8 * (4 * gm + r));
       dst[0] = lo4;
       dst[1] = hi4;
     }
-    if (g == 0) sm[wave * NH + 16 * hb + i16] = m_run[hb];
-    sl[(wave * NH + 16 * hb + i16) * 4 + g] = l_run[hb];      // the four lanes of a head share one maximum
+    if (gm == 0) sm[wave * NH + 16 * hb + i16m] = m_run[hb];
+    sl[(wave * NH + 16 * hb + i16m) * 4 + gm] = l_run[hb];      // the four lanes of a head share one maximum
   }
   __syncthreads();
   constexpr int ITERS = NH * (kD / 4) / NT;                   // float4 outputs per thread
   float fw[ITERS][NWT], lw[ITERS][NWT];
   float4 xw[ITERS][NWT];
+  const int tid_m = here(tid);
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {                        // all LDS reads first: one latency
-    const int idx = tid + it * NT;
+    const int idx = tid_m + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
 #pragma unroll
     for (int w = 0; w < NWT; ++w) {
@@ -561,7 +624,7 @@ void decode_mfma_kernel(DecodeParams p) {
   }
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    const int idx = tid + it * NT;
+    const int idx = tid_m + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
     if (head0 + hl >= sg.G) continue;
     float M = -INFINITY;
@@ -591,12 +654,34 @@ void decode_mfma_kernel(DecodeParams p) {
     }
   }
   MQA_STAMP(6);
+  if (!persist || seq_next < 0) break;
+  __syncthreads();            // the merge buffers are read: the next sequence's q operands and first round may overwrite them
+  seq = seq_next;
+  Kbuf = k_rows_of(seq);
+  Vbuf = v_rows_of(seq);
+  }
 }
 
 template <int HB, int NW, bool STAGE = false>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
-  const size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
+  size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
+  p.persist = 0;
+  if (STAGE && p.order && p.S == 1 && p.HG == 1 && p.window == 0 && !(flags & 1024)) {
+    // more ranked sequences than compute units: one workgroup per compute unit, several sequences each
+    static int ncu[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (ncu[dev] == 0) {
+      int n = 0;
+      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
+      ncu[dev] = n;
+    }
+    if (ncu[dev] > 0 && p.nseq > ncu[dev]) {
+      p.persist = ncu[dev];
+      nblocks = (size_t)ncu[dev];
+    }
+  }
   constexpr int TEAMS = STAGE ? 2 : 1;
   constexpr int NWT = NW / TEAMS;
   p.merge_alias = (nblocks > 256 || STAGE) ? 1 : 0;      // more workgroups than CUs: keep LDS small
