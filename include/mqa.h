@@ -84,7 +84,9 @@ typedef struct {
                        at most 128 positions in launches of 512 workgroups or
                        more), bit 9: never 2; bit 10: one workgroup per sequence even
                        where the 64-head form would keep one workgroup per
-                       compute unit going over several ranked sequences;
+                       compute unit going over several ranked sequences; bit 11:
+                       rank by a separate launch even where that kernel would
+                       rank up to 1024 sequences itself;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;

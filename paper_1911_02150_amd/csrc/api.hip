@@ -170,11 +170,18 @@ int decode_impl(const float* q, const void* K, const void* V, const int32_t* len
   const size_t order_off = ((pl.S > 1 ? partial_bytes((long long)nseq * G, pl.S, v) : 0) + 15) & ~(size_t)15;
   const bool worth_it = (long long)nseq * pl.S * pl.HG >= kOrderedMinBlocks &&
                         (long long)nseq * cap * (k + v) * 2 >= kOrderedMinBytes;
-  const bool ordered = pl.use_mfma && window == 0 && causal_n == 0 && !(tn.flags & 32) && nseq <= kMaxOrdered &&
-                       (worth_it || (tn.flags & 64)) && workspace && !misaligned(workspace) &&
-                       workspace_bytes >= order_off + (size_t)nseq * sizeof(int32_t);
+  const bool rank_wanted = pl.use_mfma && window == 0 && causal_n == 0 && !(tn.flags & 32) && nseq <= kMaxOrdered &&
+                           (worth_it || (tn.flags & 64));
+  const bool order_fits = workspace && !misaligned(workspace) &&
+                          workspace_bytes >= order_off + (size_t)nseq * sizeof(int32_t);
+  // more than 32 heads and more sequences than compute units: one workgroup per compute unit goes over
+  // several ranked sequences, and up to 1024 sequences it ranks them itself (no ranking launch, no workspace)
+  int inline_rank = 0;
+  const int persistent = rank_wanted ? mfma_persistent_workgroups(nseq, G, pl.S, pl.HG, window, causal_n, tn.flags, &inline_rank) : 0;
+  const bool ordered = rank_wanted && !(persistent && inline_rank) && order_fits;
   int32_t* order = ordered ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + order_off) : nullptr;
   p.order = order;
+  p.persist = (persistent && (inline_rank || ordered)) ? persistent : 0;
 #ifdef MQA_TIMELINE
   p.timeline = g_timeline;
 #endif

@@ -44,8 +44,9 @@ struct DecodeParams {
   int S;                 // ranges per sequence
   int HG;                // head groups per sequence (MFMA kernel: ceil(G / (16*HB)))
   int merge_alias;       // MFMA kernel: 1 = the wave-merge buffers re-use the q operands' LDS
-  int persist;           // MFMA kernel, 64-head form with `order`: > 0 = that many workgroups (the grid) each take
-                         // several ranked sequences in turn instead of one workgroup per sequence
+  int persist;           // MFMA kernel, 64-head form: > 0 = that many workgroups (the grid) each take several ranked
+                         // sequences in turn instead of one workgroup per sequence; the ranking is `order`, or, if
+                         // that is null, made by every workgroup for itself
   float qscale;          // scale * log2(e): logits are kept in the log2 domain
   // MFMA kernel, two-segment launches only: workgroups [nblocks0, grid) work on seg1 instead of
   // the fields above (same q, o and partial-state rows)
@@ -84,6 +85,7 @@ struct Tuning {
 // decode_mfma.hip: bf16 cache, k = v = 128; 16 or 32 heads per workgroup.
 bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap);
 int mfma_heads_per_block(int G, int flags, int causal);
+int mfma_persistent_workgroups(int nseq, int G, int S, int HG, int window, int causal, int flags, int* inline_rank);
 hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st);
 // both segments in one launch (p.seg1 filled in, 32 heads per workgroup in both); p.order must be null
 hipError_t launch_decode_mfma_two(const DecodeParams& p, long long nblocks0, long long nblocks1, hipStream_t st);

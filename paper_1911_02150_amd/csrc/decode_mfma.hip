@@ -102,6 +102,95 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& hi, u32x4& lo
   }
 }
 
+// The persistent form without a ranking launch: every workgroup ranks the sequences by length for
+// itself -- a counting sort over 1024 length classes in LDS, which is free before the first
+// sequence is staged; equal classes by sequence index, so that all workgroups arrive at the same
+// order whatever order their LDS atomics complete in -- and keeps the sequences of its own turns
+// (ranks bid, 2N-1-bid, 2N+bid, ... for N workgroups).  512 threads, nseq <= 1024, at most
+// kMaxTurns turns.  Batches of equal lengths (one class) keep the given order.
+constexpr int kMaxTurns = 4;
+constexpr int kMaxInlineRanked = 1024;
+__device__ __forceinline__ void rank_own_sequences(const int32_t* lens, int lens_div, int nseq, int cap, int nwg,
+                                                   int bid, unsigned char* smem, int (&mine)[kMaxTurns]) {
+  int* s_cnt = reinterpret_cast<int*>(smem);   // [1024] members of a class, then the first rank of the class
+  int* s_fill = s_cnt + 1024;                  // [1024] members placed so far
+  int* s_bkt = s_fill + 1024;                  // [1024] the members class by class, in order of arrival
+  int* s_ord = s_bkt + 1024;                   // [1024] the ranking
+  int* s_tot = s_ord + 1024;                   // [8] wave totals of the prefix sum
+  int* s_min = s_tot + 8;                      // [8], [8] smallest / largest class seen by a wave
+  int* s_max = s_min + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float per_pos = 1023.0f / (float)cap;
+  int cls[2];
+  int lo = 1023, hi = 0;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int i = tid + 512 * u;
+    cls[u] = -1;
+    if (i < nseq) {
+      int L = lens[i / lens_div];
+      L = L < 0 ? 0 : (L > cap ? cap : L);
+      cls[u] = 1023 - min(1023, (int)((float)L * per_pos));        // class 0 holds the longest
+      lo = min(lo, cls[u]);
+      hi = max(hi, cls[u]);
+    }
+    s_cnt[i] = 0;
+    s_fill[i] = 0;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    lo = min(lo, __shfl_xor(lo, off));
+    hi = max(hi, __shfl_xor(hi, off));
+  }
+  if (lane == 0) { s_min[wave] = lo; s_max[wave] = hi; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < 8; ++w) { lo = min(lo, s_min[w]); hi = max(hi, s_max[w]); }
+  auto rank_of_turn = [&](int t) { return t * nwg + ((t & 1) ? nwg - 1 - bid : bid); };
+  if (lo >= hi) {                              // one class: the given order
+#pragma unroll
+    for (int t = 0; t < kMaxTurns; ++t) mine[t] = rank_of_turn(t) < nseq ? rank_of_turn(t) : -1;
+    __syncthreads();                           // (s_min / s_max are read: LDS may be re-used)
+    return;
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    if (cls[u] >= 0) atomicAdd(&s_cnt[cls[u]], 1);
+  __syncthreads();
+  // exclusive prefix sum over the classes: thread t owns classes 2t and 2t+1
+  const int x0 = s_cnt[2 * tid], x1 = s_cnt[2 * tid + 1];
+  int incl = x0 + x1;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(incl, off);
+    if (lane >= off) incl += y;
+  }
+  if (lane == 63) s_tot[wave] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += s_tot[w];
+  const int excl = before + incl - (x0 + x1);
+  s_cnt[2 * tid] = excl;
+  s_cnt[2 * tid + 1] = excl + x0;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    if (cls[u] >= 0) s_bkt[s_cnt[cls[u]] + atomicAdd(&s_fill[cls[u]], 1)] = tid + 512 * u;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+    if (cls[u] >= 0) {
+      const int i = tid + 512 * u, base = s_cnt[cls[u]], n = s_fill[cls[u]];
+      int r = base;
+      for (int m2 = 0; m2 < n; ++m2) r += (s_bkt[base + m2] < i) ? 1 : 0;     // inside a class: by index
+      s_ord[r] = i;
+    }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < kMaxTurns; ++t) mine[t] = rank_of_turn(t) < nseq ? s_ord[rank_of_turn(t)] : -1;
+  __syncthreads();                             // LDS is handed on to the q operands and the staged rounds
+}
+
 #ifdef MQA_TIMELINE   // debug builds: per-wave wall-clock stamps (100 MHz counter shared by all CUs)
 #define MQA_STAMP(i) do { if (p.timeline && lane == 0) p.timeline[((size_t)blockIdx.x * NW + (threadIdx.x >> 6)) * 8 + (i)] = wall_clock64(); } while (0)
 #else
@@ -151,9 +240,19 @@ void decode_mfma_kernel(DecodeParams p) {
   // while the current one's last rows are still being worked on.
   const bool persist = STAGE && p.persist > 0;
   int pass = 0;
+  int mine[kMaxTurns] = {-1, -1, -1, -1};       // persistent form without a ranking launch: this workgroup's sequences
   if (persist) {
     hg = srange = 0;
-    seq = p.order[bid];
+    if (p.order) {
+      seq = p.order[bid];
+    } else {
+      if constexpr (STAGE) {
+        rank_own_sequences(sg.lens, sg.lens_div, p.nseq, sg.cap, p.persist, bid, smem_raw, mine);
+#pragma unroll
+        for (int t = 0; t < kMaxTurns; ++t) mine[t] = __builtin_amdgcn_readfirstlane(mine[t]);      // (the same in every lane)
+      }
+      seq = mine[0];
+    }
   } else if (p.order) {
     // Longest-first schedule: workgroups are dispatched in index order, round-robin over the
     // 8 XCDs, so XCD x takes the sequences ranked x, x+8, ... by length, longest first, and all
@@ -330,8 +429,12 @@ void decode_mfma_kernel(DecodeParams p) {
   int L = started ? L_next : sg.lens[seq / sg.lens_div];
   if (persist) {              // which sequence comes after this one: asked for now, needed a round before this one ends
     ++pass;
-    const int rank = pass * p.persist + ((pass & 1) ? p.persist - 1 - bid : bid);
-    seq_next = rank < p.nseq ? p.order[rank] : -1;
+    if (p.order) {
+      const int rank = pass * p.persist + ((pass & 1) ? p.persist - 1 - bid : bid);
+      seq_next = rank < p.nseq ? p.order[rank] : -1;
+    } else {
+      seq_next = pass == 1 ? mine[1] : pass == 2 ? mine[2] : pass == 3 ? mine[3] : -1;
+    }
   }
   L = L < 0 ? 0 : (L > sg.cap ? sg.cap : L);
   // Local attention (the paper's Section 4.1 variant): only positions [lo, L) count; the ranges
@@ -666,22 +769,8 @@ template <int HB, int NW, bool STAGE = false>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
   size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
-  p.persist = 0;
-  if (STAGE && p.order && p.S == 1 && p.HG == 1 && p.window == 0 && !(flags & 1024)) {
-    // more ranked sequences than compute units: one workgroup per compute unit, several sequences each
-    static int ncu[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    if (ncu[dev] == 0) {
-      int n = 0;
-      if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
-      ncu[dev] = n;
-    }
-    if (ncu[dev] > 0 && p.nseq > ncu[dev]) {
-      p.persist = ncu[dev];
-      nblocks = (size_t)ncu[dev];
-    }
-  }
+  if (!STAGE) p.persist = 0;
+  if (p.persist > 0) nblocks = (size_t)p.persist;      // one workgroup per compute unit, several sequences each
   constexpr int TEAMS = STAGE ? 2 : 1;
   constexpr int NWT = NW / TEAMS;
   p.merge_alias = (nblocks > 256 || STAGE) ? 1 : 0;      // more workgroups than CUs: keep LDS small
@@ -729,6 +818,25 @@ bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap) {
 // (plain decode and local attention), or groups of 32 (causal rows, or by a tuning flag)
 int mfma_heads_per_block(int G, int flags, int causal) {
   return G <= 16 ? 16 : (G > 32 && !(flags & 8) && !causal) ? 64 : 32;
+}
+
+// The persistent form of the 64-head kernel applies to a ranked batch of more sequences than
+// compute units with one range and one head group per sequence: returns the number of workgroups
+// (one per compute unit), else 0.  *inline_rank: the kernel can rank the sequences itself.
+int mfma_persistent_workgroups(int nseq, int G, int S, int HG, int window, int causal, int flags, int* inline_rank) {
+  *inline_rank = 0;
+  if (mfma_heads_per_block(G, flags, causal) != 64 || S != 1 || HG != 1 || window != 0 || (flags & 1024)) return 0;
+  static int ncu[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  if (ncu[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
+    ncu[dev] = n;
+  }
+  if (ncu[dev] <= 0 || nseq <= ncu[dev]) return 0;
+  *inline_rank = (nseq <= kMaxInlineRanked && nseq <= kMaxTurns * ncu[dev] && !(flags & 2048)) ? 1 : 0;
+  return ncu[dev];
 }
 
 hipError_t launch_decode_mfma_two(const DecodeParams& p_in, long long nblocks0, long long nblocks1, hipStream_t st) {

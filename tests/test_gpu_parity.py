@@ -568,12 +568,14 @@ def test_prefill_prompt_then_decode(m):
 # ----------------------------------------------------------------- longest-first scheduling of ragged batches
 @pytest.mark.parametrize("b,h,cap,multi_head,splits", [(1030, 8, 96, False, 0), (515, 40, 160, False, 0), (5, 8, 300, False, 0),
                                                        (131, 8, 70, True, 0), (300, 16, 256, False, 4),
-                                                       (300, 64, 200, False, 0), (1100, 48, 130, False, 0), (257, 33, 40, False, 0)])
+                                                       (300, 64, 200, False, 0), (1100, 48, 130, False, 0), (257, 33, 40, False, 0),
+                                                       (1024, 64, 70, False, 0), (700, 64, 100, False, 0)])
 def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, splits):
     """Large batches are started longest sequence first (a ranking pass orders the groups; the grid
     is padded to a multiple of 8 groups); forced here on small ones.  With more than 32 heads and
     more sequences than compute units, one workgroup per compute unit goes over several ranked
-    sequences (2, 3 and 5 turns here, some of them empty sequences).  Outputs must equal the
+    sequences (2, 3 and 5 turns here, some of them empty sequences), ranking up to 1024 sequences
+    itself and taking the ranking pass's order beyond that.  Outputs must equal the
     oracle's and be bit-identical to the unscheduled launch and to one workgroup per sequence."""
     c = mi.random_case(40 + b, b, h, cap, 128, 128, cache="bf16", lens="with_zero", multi_head=multi_head)
     tn = dict(splits=splits) if splits else {}
@@ -582,6 +584,26 @@ def test_longest_first_schedule_changes_no_result(m, b, h, cap, multi_head, spli
     o_plain, _ = run_case(m, c, multi_head, tuning=dict(tn, flags=32))
     assert torch.equal(o, o_plain)
     o_each, _ = run_case(m, c, multi_head, tuning=dict(tn, flags=64 | 1024))
+    assert torch.equal(o, o_each)
+    o_launch, _ = run_case(m, c, multi_head, tuning=dict(tn, flags=64 | 2048))      # ranked by the separate launch
+    assert torch.equal(o, o_launch)
+
+
+@pytest.mark.parametrize("pattern", ["all_equal", "two_values", "one_short"])
+def test_ranking_inside_the_kernel_with_equal_lengths(m, pattern):
+    """Every workgroup of the persistent form ranks the sequences for itself; equal lengths must be
+    ranked the same way by all of them (else a sequence is done twice and another not at all)."""
+    b, h, cap = 600, 64, 64
+    lens = np.full(b, cap, dtype=np.int32)
+    if pattern == "two_values":
+        lens[::2] = 17
+        lens[5] = 0
+    elif pattern == "one_short":
+        lens[333] = 3
+    c = mi.random_case(77, b, h, cap, 128, 128, cache="bf16", lens=lens)
+    o, ref = run_case(m, c, False, tuning=dict(flags=64))
+    check(o, ref, "bf16", f"ranked in the kernel, {pattern}")
+    o_each, _ = run_case(m, c, False, tuning=dict(flags=64 | 1024))
     assert torch.equal(o, o_each)
 
 
