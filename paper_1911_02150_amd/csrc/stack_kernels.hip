@@ -35,6 +35,41 @@ void layernorm_kernel(const float* __restrict__ x, float* __restrict__ y, int d,
   for (int i = threadIdx.x; i < d; i += 256) yr[i] = (xr[i] - mean) * rstd;
 }
 
+// The same for rows of a multiple of 4 and at most 256 * 4 * NV floats: the row is read once, with
+// 16-byte loads all in flight together, and kept in registers for the mean, the centred sum of
+// squares and the result (the rows of a decode step are few: the launch is one memory round trip).
+template <int NV>
+__global__ __launch_bounds__(256)
+void layernorm_rows_kernel(const float* __restrict__ x, float* __restrict__ y, int d, float eps) {
+  __shared__ float red[4];
+  const float4* xr = reinterpret_cast<const float4*>(x + (size_t)blockIdx.x * d);
+  float4* yr = reinterpret_cast<float4*>(y + (size_t)blockIdx.x * d);
+  const int d4 = d >> 2;
+  float4 r[NV];
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = threadIdx.x + 256 * u;
+    r[u] = i < d4 ? xr[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) s += (r[u].x + r[u].y) + (r[u].z + r[u].w);
+  const float mean = block_sum(s, red) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int u = 0; u < NV; ++u)
+    if (threadIdx.x + 256 * u < d4) {
+      const float a = r[u].x - mean, b = r[u].y - mean, c = r[u].z - mean, e = r[u].w - mean;
+      q += (a * a + b * b) + (c * c + e * e);
+    }
+  const float rstd = 1.0f / sqrtf(block_sum(q, red) / d + eps);
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = threadIdx.x + 256 * u;
+    if (i < d4) yr[i] = make_float4((r[u].x - mean) * rstd, (r[u].y - mean) * rstd, (r[u].z - mean) * rstd, (r[u].w - mean) * rstd);
+  }
+}
+
 // x[row] = E[token[row]] + P[pos[row]]; indices outside the tables are clamped (they live on the
 // device, so the host cannot reject them)
 __global__ __launch_bounds__(256)
@@ -101,7 +136,9 @@ void argmax_kernel(const float* __restrict__ x, int32_t* __restrict__ out, int n
 }  // namespace
 
 hipError_t launch_layernorm(const float* x, float* y, int rows, int d, float eps, hipStream_t st) {
-  hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(256), 0, st, x, y, d, eps);
+  if ((d & 3) == 0 && d <= 1024) hipLaunchKernelGGL(layernorm_rows_kernel<1>, dim3(rows), dim3(256), 0, st, x, y, d, eps);
+  else if ((d & 3) == 0 && d <= 4096) hipLaunchKernelGGL(layernorm_rows_kernel<4>, dim3(rows), dim3(256), 0, st, x, y, d, eps);
+  else hipLaunchKernelGGL(layernorm_kernel, dim3(rows), dim3(256), 0, st, x, y, d, eps);
   return hipGetLastError();
 }
 hipError_t launch_embed(const int32_t* tokens, const int32_t* pos, const float* E, const float* P, float* x,

@@ -33,6 +33,10 @@ def test_stack_glue_kernels(m):
     x = g.standard_normal((37, 1000), dtype=np.float32) * np.float32(3) + np.float32(0.5)
     dx = torch.from_numpy(x).to(DEV)
     assert np.max(np.abs(m.mqa_stack_layernorm(dx).cpu().numpy() - ods.layernorm(x))) <= 1e-5
+    for rows, d in ((5, 1024), (3, 2504), (2, 4096), (3, 4100), (4, 1002), (2, 8)):      # register-resident rows, long rows, odd widths
+        xs = g.standard_normal((rows, d), dtype=np.float32) * np.float32(2) - np.float32(1.5)
+        got = m.mqa_stack_layernorm(torch.from_numpy(xs).to(DEV)).cpu().numpy()
+        assert np.max(np.abs(got - ods.layernorm(xs))) <= 1e-5, (rows, d)
     E = g.standard_normal((50, 64), dtype=np.float32)
     P = g.standard_normal((9, 64), dtype=np.float32)
     tok = g.integers(0, 50, size=11).astype(np.int32)
