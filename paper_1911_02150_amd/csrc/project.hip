@@ -235,42 +235,49 @@ void project_qkv_append_kernel(const float* __restrict__ x, const float* __restr
                                const float* __restrict__ P_k, const float* __restrict__ P_v,
                                float* __restrict__ q, CT* __restrict__ K, CT* __restrict__ V,
                                const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
-                               int rows, int d, int h, int h_kv, int cap, int k, int v, int tile0, int mem_rows) {
+                               int rows, int d, int h, int h_kv, int cap, int k, int v, int nq_tiles, int kv_narrow,
+                               int mem_rows) {
   constexpr int TM = RB * T, TN = CB * T;
   __shared__ __align__(16) double red_raw[NWAVES * T * TN];       // = RB <= 2 float32 row blocks
   static_assert(RB <= 2, "a q tile's float32 partial tiles must fit the float64 buffer");
   const int row0 = blockIdx.y * TM;
-  const int ctile = blockIdx.x + tile0;
-  int n0 = ctile * TN;
   const int nq = h * k, nk = h_kv * k;
-  int which = 0;                       // 0: q, 1: K row, 2: V row
-  if (n0 >= nq + nk) { which = 2; n0 -= nq + nk; }
-  else if (n0 >= nq) { which = 1; n0 -= nq; }
-  const int kv = which == 2 ? v : k;
-  if (which == 0) {
+  if ((int)blockIdx.x < nq_tiles) {    // a tile of q
+    const int n0 = blockIdx.x * TN;
     float (*red)[TM * TN] = reinterpret_cast<float (*)[TM * TN]>(red_raw);
-    gemm_tile<false, T, RB, CB>(x, P_q, rows, d, h, kv, row0, n0, red);
+    gemm_tile<false, T, RB, CB>(x, P_q, rows, d, h, k, row0, n0, red);
     for (int e = threadIdx.x; e < TM * TN; e += NWAVES * 64) {
       const int r = e / TN, c = e % TN;
       if (row0 + r < rows) q[(size_t)(row0 + r) * nq + n0 + c] = sum_partials(&red[0][0], e, TM * TN);
     }
     return;
   }
-  double (*red)[T * TN] = reinterpret_cast<double (*)[T * TN]>(red_raw);
+  // A tile of the K or V rows.  Their float64 products run at half the matrix rate, so for few
+  // rows (a decode step) the tiles are a single block of 16 columns wide: four times the
+  // workgroups, a quarter of the time each; for many rows (a prompt) they keep the q tiles' width
+  // and with it the re-use of the input rows.
+  const int kvt = blockIdx.x - nq_tiles;
+  const int width = kv_narrow ? T : TN;
+  int n0 = kvt * width;
+  const int which = n0 >= nk ? 2 : 1;      // 1: K row, 2: V row
+  if (which == 2) n0 -= nk;
+  const int kv = which == 2 ? v : k;
   CT* dst = which == 1 ? K : V;
+  const float* P = which == 1 ? P_k : P_v;
   for (int rb = 0; rb < RB && row0 + rb * T < rows; ++rb) {
     if (rb) __syncthreads();           // the previous row block's sums have been read
-    gemm_tile<false, T, 1, CB, double>(x, which == 1 ? P_k : P_v, rows, d, h_kv, kv, row0 + rb * T, n0, red);
-    for (int e = threadIdx.x; e < T * TN; e += NWAVES * 64) {
-      const int row = row0 + rb * T + e / TN, n = n0 + e % TN;
+    if (kv_narrow) gemm_tile<false, T, 1, 1, double>(x, P, rows, d, h_kv, kv, row0 + rb * T, n0, reinterpret_cast<double (*)[T * T]>(red_raw));
+    else gemm_tile<false, T, 1, CB, double>(x, P, rows, d, h_kv, kv, row0 + rb * T, n0, reinterpret_cast<double (*)[T * TN]>(red_raw));
+    for (int e = threadIdx.x; e < T * width; e += NWAVES * 64) {
+      const int row = row0 + rb * T + e / width, n = n0 + e % width;
       if (row >= rows) continue;
       const int seq = mem_rows > 0 ? row / mem_rows : row;
       const int L = mem_rows > 0 ? row - seq * mem_rows : lens_in[row];
       if (L < 0 || L >= cap) continue;
-      dst[(((size_t)seq * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(sum_partials(&red[0][0], e, T * TN));
+      dst[(((size_t)seq * h_kv + n / kv) * cap + L) * kv + (n % kv)] = cache_value<CT>(sum_partials(red_raw, e, T * width));
     }
   }
-  if (ctile * TN == nq && threadIdx.x < TM && row0 + threadIdx.x < rows) {      // the first K tile of each row tile
+  if (kvt == 0 && threadIdx.x < TM && row0 + threadIdx.x < rows) {      // the first K tile of each row tile
     const int row = row0 + threadIdx.x;
     if (mem_rows > 0) {
       if (row % mem_rows == 0) {
@@ -357,16 +364,19 @@ hipError_t launch_project_qkv_append(const float* x, const float* P_q, const flo
   int g = k, r = v;
   while (r) { const int t2 = g % r; g = r; r = t2; }
   const Tile t = pick_tile(q_done ? ntot - nq : ntot, rows, g);
+  // a decode step's rows and K / V columns that are a small part of the product (multi-query): K / V tiles of
+  // 16 columns (b=128, h=8: 14.2 -> 10.4 us; multi-head, where they are two thirds of it: 25.9 -> 31.6 us, so not there)
+  const int kv_narrow = (rows <= 512 && 2 * (ntot - nq) <= nq) ? 1 : 0;
   const dim3 block(NWAVES * 64);
   bool launched = false;
 #define MQA_QKV(RB_, CB_)                                                                                            \
   if (!launched && t.RB == RB_ && t.CB == CB_) {                                                                     \
-    const int tile0 = q_done ? nq / (CB_ * 16) : 0;                                                                  \
-    const dim3 grid(ntot / (CB_ * 16) - tile0, (rows + RB_ * 16 - 1) / (RB_ * 16));                                  \
+    const int nq_tiles = q_done ? 0 : nq / (CB_ * 16);                                                               \
+    const dim3 grid(nq_tiles + (ntot - nq) / (kv_narrow ? 16 : CB_ * 16), (rows + RB_ * 16 - 1) / (RB_ * 16));       \
     if (is_bf16) hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, uint16_t>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0, mem_rows); \
+                                    (uint16_t*)K, (uint16_t*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, nq_tiles, kv_narrow, mem_rows); \
     else hipLaunchKernelGGL((project_qkv_append_kernel<16, RB_, CB_, float>), grid, block, 0, st, x, P_q, P_k, P_v, q, \
-                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, tile0, mem_rows);  \
+                            (float*)K, (float*)V, lens_in, lens_out, rows, d, h, h_kv, cap, k, v, nq_tiles, kv_narrow, mem_rows);  \
     launched = true;                                                                                                 \
   }
   MQA_TILES(MQA_QKV)
