@@ -7,13 +7,14 @@
 //
 // Work decomposition
 //   grid  = nseq * S * HG workgroups (sequence, position range, group of 16*HB heads; HB = 1 or 2).
-//           More than 32 heads are split into head groups: the groups of one (sequence, range)
-//           are neighbouring work items on one XCD and read the same tiles at about the same
-//           time, so with cacheable loads the second read is served by L2.  (Two teams of waves
-//           in one workgroup measured slower.)
-//           With an order array (ragged batches) the sequences are taken longest first.
-//   block = NW independent wavefronts; wave w takes the 32-position tiles
-//           w, w+NW, ... of the range, so the block streams its range front to back.
+//           More than 32 heads: the STAGE form (64 heads per workgroup, see the end of this
+//           comment), or, for causal rows and by a tuning flag, head groups of 32 as neighbouring
+//           work items on one XCD that read the same tiles at about the same time, so that with
+//           cacheable loads the second read is served by L2.
+//           With an order array (ragged batches) the sequences are taken longest first; the STAGE
+//           form then runs one workgroup per compute unit over several sequences.
+//   block = NW wavefronts (2, 4 or 8), independent of each other up to 32 heads; wave w takes the
+//           32-position tiles w, w+NW, ... of the range, so the block streams its range front to back.
 //   Each wave keeps, for all 16*HB heads, a running maximum, a running sum and
 //   the un-normalised output O^T [128 x 16*HB] in MFMA accumulators.  At the end
 //   the NW partial states are merged through LDS and written either as the
@@ -74,13 +75,6 @@ constexpr float kSlack = 8.f;        // log2 of the largest softmax weight kept 
 __device__ __forceinline__ floatx4 mfma16(const u32x4& a, const u32x4& b, const floatx4& c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-
-// Cache rows are read exactly once per step: non-temporal loads keep them from
-// displacing anything in L2 / Infinity Cache and measurably raise HBM read throughput.
-template <bool NTL> __device__ __forceinline__ u32x4 ld16(const u32x4* p) {
-  if (NTL) return __builtin_nontemporal_load(p);
-  return *p;
 }
 
 // two floats -> packed bf16 pair (round to nearest even; one v_cvt_pk_bf16_f32)
@@ -297,7 +291,9 @@ void decode_mfma_kernel(DecodeParams p) {
   __amdgpu_buffer_rsrc_t Kbuf = k_rows_of(seq), Vbuf = v_rows_of(seq);
   const uint32_t klane = (uint32_t)(krow_in_tile * kRowU4 + g) * 16u;      // row krow_in_tile, 16-byte chunk g
   const uint32_t vlane = (uint32_t)(g * kRowU4 + i16) * 16u;               // row g, 16-byte chunk i16
-  constexpr int kAuxK = NTL ? 2 : 0, kAuxV = NTL ? 2 : 0;                   // non-temporal hint
+  // Cache rows are read exactly once per step: the non-temporal hint keeps them from displacing
+  // anything in L2 / Infinity Cache and measurably raises HBM read throughput.
+  constexpr int kAuxK = NTL ? 2 : 0, kAuxV = NTL ? 2 : 0;
   auto tile_offset = [&](int t, bool wanted) -> uint32_t {                  // wave-uniform
     return wanted ? (uint32_t)(begin + 32 * t) * (uint32_t)(kRowU4 * 16) : kNoTile;
   };
