@@ -86,7 +86,9 @@ typedef struct {
                        where the 64-head form would keep one workgroup per
                        compute unit going over several ranked sequences; bit 11:
                        rank by a separate launch even where that kernel would
-                       rank up to 1024 sequences itself;
+                       rank up to 1024 sequences itself; bit 12: causal rows
+                       (prompt pass) in workgroups of 32 rows whose waves split
+                       the tiles instead of 128 rows, 32 per wave;
                        bit 5: never, bit 6: always schedule the longest sequences
                        first (default: only for large ragged-capable batches)    */
 } mqa_tuning;

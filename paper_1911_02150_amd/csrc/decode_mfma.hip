@@ -200,17 +200,23 @@ __device__ __forceinline__ void rank_own_sequences(const int32_t* lens, int lens
 // tile read it from LDS, where all eight waves put a round of four tiles (128 positions, 64 KiB)
 // with coalesced 16-byte loads of whole rows, one round ahead in registers.  Each byte of the
 // cache is requested from L2 once per workgroup, whatever the number of heads.
-template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false, bool STAGE = false>
+//
+// ROWS: the form for causal rows (a prompt's n queries x h heads per sequence).  Every wave is a
+// team of its own: it takes 16*HB of the workgroup's NW*16*HB rows and all tiles up to those rows'
+// limits, so nothing is merged between waves and a workgroup's fixed costs (launch, q staging,
+// output) are spread over NW times the rows.
+template <int HB, int NW, bool QSPLIT, bool PSPLIT, bool NTL, bool TWO_SEG = false, bool STAGE = false, bool ROWS = false>
 __global__ __launch_bounds__(NW * 64, STAGE ? 1 : 2)
 void decode_mfma_kernel(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   static_assert(!STAGE || (HB == 2 && NW == 8 && !TWO_SEG), "the staged form is two teams of four waves, 32 heads each");
-  constexpr int TEAMS = STAGE ? 2 : 1;
+  static_assert(!ROWS || (!STAGE && !TWO_SEG), "one form at a time");
+  constexpr int TEAMS = STAGE ? 2 : ROWS ? NW : 1;
   constexpr int NWT = NW / TEAMS;             // waves per team: they share the team's heads and split the tiles
   constexpr int NT = NWT * 64;                // threads per team
   constexpr int NH = 16 * HB;                 // heads handled by a team
   const int lane = threadIdx.x & 63;
-  const int team = STAGE ? (int)(threadIdx.x >> 8) : 0;
+  const int team = TEAMS > 1 ? (int)threadIdx.x / NT : 0;
   const int tid = threadIdx.x - team * NT, wave = tid >> 6;      // thread and wave inside the team
   const int i16 = lane & 15, g = lane >> 4;
 
@@ -462,7 +468,9 @@ void decode_mfma_kernel(DecodeParams p) {
   }
   const int end = min(begin + sg.chunk, lim_max);
   const int mask_from = min(end, lim_min);        // tiles reaching beyond this position need masking
-  if (end <= begin) {
+  // (ROWS: the other waves of the workgroup have their own limits and wait at the barriers below, so a wave
+  // with nothing to see goes on with no tiles and writes its zero rows at the end like any other)
+  if (!ROWS && end <= begin) {
     if (p.PS == 0) {          // empty sequence: zero output rows
       for (int idx = here(tid); idx < NH * (kD / 4); idx += NT) {
         int hl = idx / (kD / 4), c4 = idx % (kD / 4);
@@ -478,7 +486,7 @@ void decode_mfma_kernel(DecodeParams p) {
     Vbuf = v_rows_of(seq);
     continue;
   }
-  const int ntiles = (end - begin + 31) >> 5;
+  const int ntiles = end > begin ? (end - begin + 31) >> 5 : 0;
   const int nrounds = (ntiles + 3) >> 2;           // (64-head form)
   // Load slot s of a sequence fetches its round s; the slot after the last round is used, in the
   // persistent form, for the next sequence's first round (its q and length are requested when the
@@ -684,9 +692,9 @@ void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) l_run[hb] = 0.25f * accl[hb][0];
   }
-  if (p.merge_alias || STAGE) __syncthreads();
+  if (p.merge_alias || TEAMS > 1) __syncthreads();
   constexpr int kMergeFloats = NWT * NH * kOPitch + 5 * NWT * NH;                        // per team
-  float* so = reinterpret_cast<float*>(smem_raw + ((p.merge_alias || STAGE) ? 0 : QOPS * 16 * 2)) + team * kMergeFloats;   // [NWT][NH][kOPitch]
+  float* so = reinterpret_cast<float*>(smem_raw + ((p.merge_alias || TEAMS > 1) ? 0 : QOPS * 16 * 2)) + team * kMergeFloats;   // [NWT][NH][kOPitch]
   float* sm = so + NWT * NH * kOPitch;                      // [NWT][NH]     running maxima
   float* sl = sm + NWT * NH;                                // [NWT][NH][4]  sums, one per lane group g
   const int lane_m = here(lane), i16m = lane_m & 15, gm = lane_m >> 4;
@@ -761,15 +769,15 @@ void decode_mfma_kernel(DecodeParams p) {
   }
 }
 
-template <int HB, int NW, bool STAGE = false>
+template <int HB, int NW, bool STAGE = false, bool ROWS = false>
 hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   DecodeParams p = p_in;
   size_t nblocks = (p.order ? (size_t)((p.nseq + 7) / 8) * 8 : (size_t)p.nseq) * p.S * p.HG;
   if (!STAGE) p.persist = 0;
   if (p.persist > 0) nblocks = (size_t)p.persist;      // one workgroup per compute unit, several sequences each
-  constexpr int TEAMS = STAGE ? 2 : 1;
+  constexpr int TEAMS = STAGE ? 2 : ROWS ? NW : 1;
   constexpr int NWT = NW / TEAMS;
-  p.merge_alias = (nblocks > 256 || STAGE) ? 1 : 0;      // more workgroups than CUs: keep LDS small
+  p.merge_alias = (nblocks > 256 || TEAMS > 1) ? 1 : 0;      // more workgroups than CUs: keep LDS small
   const size_t q_bytes = (size_t)TEAMS * HB * 4 * 64 * 16 * 2;
   const size_t merge_bytes = (size_t)TEAMS * ((size_t)NWT * 16 * HB * kOPitch + 5 * NWT * 16 * HB) * sizeof(float);
   const size_t work_bytes = q_bytes + (STAGE ? 4 * 128 * kRowU4 * 16 : 0);     // q operands (+ two rounds of K and V)
@@ -778,8 +786,8 @@ hipError_t launch_hb(const DecodeParams& p_in, int flags, hipStream_t st) {
   const dim3 grid((unsigned)nblocks), block(NW * 64);
   void (*kern)(DecodeParams);
   // Non-temporal loads unless the tiles are meant to be found in L2 by a second head group.
-  const bool ntl = !(flags & 4) && (p.HG == 1 || STAGE);
-#define MQA_PICK(QS, PS) (ntl ? decode_mfma_kernel<HB, NW, QS, PS, true, false, STAGE> : decode_mfma_kernel<HB, NW, QS, PS, false, false, STAGE>)
+  const bool ntl = !(flags & 4) && (p.HG == 1 || STAGE) && !ROWS;
+#define MQA_PICK(QS, PS) (ntl ? decode_mfma_kernel<HB, NW, QS, PS, true, false, STAGE, ROWS> : decode_mfma_kernel<HB, NW, QS, PS, false, false, STAGE, ROWS>)
   switch (flags & 3) {
     case 0: kern = MQA_PICK(true, true); break;
     case 1: kern = MQA_PICK(false, true); break;
@@ -813,6 +821,7 @@ bool mfma_shape_ok(int G, int k, int v, int is_bf16, int cap) {
 // 16 or 32 heads per workgroup; more than 32 heads: the staged form with 64 heads per workgroup
 // (plain decode and local attention), or groups of 32 (causal rows, or by a tuning flag)
 int mfma_heads_per_block(int G, int flags, int causal) {
+  if (causal && G > 32 && !(flags & 4096)) return 128;      // causal rows: four waves of 32 rows each
   return G <= 16 ? 16 : (G > 32 && !(flags & 8) && !causal) ? 64 : 32;
 }
 
@@ -874,6 +883,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, int flags, hipStream_t st) 
   if (hpb == 16) return wide ? launch_hb<1, 8>(p, flags, st) : launch_hb<1, 4>(p, flags, st);
   // the staged form is bound by its arithmetic, not by HBM: single-term weights unless asked otherwise
   if (hpb == 64) return launch_hb<2, 8, true>(p, (flags & 128) ? flags : (flags | 2), st);
+  if (hpb == 128) return launch_hb<2, 4, false, true>(p, flags, st);
   return wide ? launch_hb<2, 8>(p, flags, st) : launch_hb<2, 4>(p, flags, st);
 }
 
