@@ -71,26 +71,31 @@ typedef struct {
   int32_t splits;   /* >0: number of position ranges each sequence is split into */
   int32_t kernel;   /* 0 auto, 1 force the generic kernel, 2 force the MFMA kernel
                        (MQA_ERR_SHAPE if the shape does not qualify)             */
-  int32_t flags;    /* MFMA kernel variants, 0 = default.  bit 0: single bf16 term for
-                       q; bit 1: single bf16 term for the softmax weights (both
-                       faster, less accurate); bit 2: plain instead of
-                       non-temporal cache loads; bit 3: more than 32 heads: head
-                       groups of 32 as separate workgroups instead of 64 heads
-                       per workgroup sharing each tile through LDS; bit 7: two
-                       bf16 terms for the weights in that 64-head form too (its
-                       default is one, normalised by the sum of the rounded
-                       weights); bit 4: 8 waves per workgroup; bit 8: 2 waves per
-                       workgroup for up to 16 heads (default: only for ranges of
-                       at most 128 positions in launches of 512 workgroups or
-                       more), bit 9: never 2; bit 10: one workgroup per sequence even
-                       where the 64-head form would keep one workgroup per
-                       compute unit going over several ranked sequences; bit 11:
-                       rank by a separate launch even where that kernel would
-                       rank up to 1024 sequences itself; bit 12: causal rows
-                       (prompt pass) in workgroups of 32 rows whose waves split
-                       the tiles instead of 128 rows, 32 per wave;
-                       bit 5: never, bit 6: always schedule the longest sequences
-                       first (default: only for large ragged-capable batches)    */
+  int32_t flags;    /* MFMA kernel variants, 0 = default (measurement and test switches):
+                       bit 0   single bf16 term for q (faster, less accurate)
+                       bit 1   single bf16 term for the softmax weights (likewise)
+                       bit 2   plain instead of non-temporal cache loads
+                       bit 3   more than 32 heads: head groups of 32 as separate
+                               workgroups instead of 64 heads per workgroup
+                               sharing each tile through LDS
+                       bit 4   8 waves per workgroup (up to 32 heads)
+                       bit 5   never / bit 6: always schedule the longest
+                               sequences first (default: only for large
+                               ragged-capable batches)
+                       bit 7   two bf16 terms for the weights in the 64-head
+                               form too (its default is one, normalised by the
+                               sum of the rounded weights)
+                       bit 8   2 waves per workgroup for up to 16 heads (default:
+                               only for ranges of at most 128 positions in
+                               launches of 512 workgroups or more) / bit 9: never
+                       bit 10  one workgroup per sequence even where the 64-head
+                               form would keep one workgroup per compute unit
+                               going over several ranked sequences
+                       bit 11  rank by a separate launch even where that kernel
+                               would rank up to 1024 sequences itself
+                       bit 12  causal rows (prompt pass) in workgroups of 32 rows
+                               whose waves split the tiles, instead of 128 rows,
+                               32 per wave                                       */
 } mqa_tuning;
 
 /*
