@@ -695,8 +695,8 @@ void decode_mfma_kernel(DecodeParams p) {
   if (p.merge_alias || TEAMS > 1) __syncthreads();
   constexpr int kMergeFloats = NWT * NH * kOPitch + 5 * NWT * NH;                        // per team
   float* so = reinterpret_cast<float*>(smem_raw + ((p.merge_alias || TEAMS > 1) ? 0 : QOPS * 16 * 2)) + team * kMergeFloats;   // [NWT][NH][kOPitch]
-  float* sm = so + NWT * NH * kOPitch;                      // [NWT][NH]     running maxima
-  float* sl = sm + NWT * NH;                                // [NWT][NH][4]  sums, one per lane group g
+  float* sm = so + NWT * NH * kOPitch;                      // [NH][NWT]  running maxima
+  float* sl = sm + NWT * NH;                                // [NH][NWT]  sums
   const int lane_m = here(lane), i16m = lane_m & 15, gm = lane_m >> 4;
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
@@ -709,8 +709,14 @@ void decode_mfma_kernel(DecodeParams p) {
       dst[0] = lo4;
       dst[1] = hi4;
     }
-    if (gm == 0) sm[wave * NH + 16 * hb + i16m] = m_run[hb];
-    sl[(wave * NH + 16 * hb + i16m) * 4 + gm] = l_run[hb];      // the four lanes of a head share one maximum
+    // the four lanes of a head share one maximum and hold a quarter of the sum each
+    float lq = l_run[hb];
+    lq += __shfl_xor(lq, 16);
+    lq += __shfl_xor(lq, 32);
+    if (gm == 0) {
+      sm[(16 * hb + i16m) * NWT + wave] = m_run[hb];
+      sl[(16 * hb + i16m) * NWT + wave] = lq;
+    }
   }
   __syncthreads();
   constexpr int ITERS = NH * (kD / 4) / NT;                   // float4 outputs per thread
@@ -721,13 +727,20 @@ void decode_mfma_kernel(DecodeParams p) {
   for (int it = 0; it < ITERS; ++it) {                        // all LDS reads first: one latency
     const int idx = tid_m + it * NT;
     const int hl = idx / (kD / 4), c4 = idx % (kD / 4);
+    if constexpr (NWT == 4) {                                 // a head's four maxima and four sums: one read each
+      const float4 m4 = *reinterpret_cast<const float4*>(sm + hl * 4);
+      const float4 l4 = *reinterpret_cast<const float4*>(sl + hl * 4);
+      fw[it][0] = m4.x; fw[it][1] = m4.y; fw[it][2] = m4.z; fw[it][3] = m4.w;
+      lw[it][0] = l4.x; lw[it][1] = l4.y; lw[it][2] = l4.z; lw[it][3] = l4.w;
+    } else {
 #pragma unroll
-    for (int w = 0; w < NWT; ++w) {
-      fw[it][w] = sm[w * NH + hl];
-      const float4 l4 = *reinterpret_cast<const float4*>(sl + (w * NH + hl) * 4);
-      lw[it][w] = (l4.x + l4.y) + (l4.z + l4.w);
-      xw[it][w] = reinterpret_cast<const float4*>(so + ((size_t)w * NH + hl) * kOPitch)[c4];
+      for (int w = 0; w < NWT; ++w) {
+        fw[it][w] = sm[hl * NWT + w];
+        lw[it][w] = sl[hl * NWT + w];
+      }
     }
+#pragma unroll
+    for (int w = 0; w < NWT; ++w) xw[it][w] = reinterpret_cast<const float4*>(so + ((size_t)w * NH + hl) * kOPitch)[c4];
   }
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
